@@ -1,0 +1,141 @@
+/*
+ * pdelta.h - C ABI of the 1-bit per-axis weight-delta library for AMD MI355X (gfx950).
+ *
+ * Notation follows the paper ("Per-Axis Weight Deltas for Frequent Model Updates", Section 2):
+ *   W_b, W_f  base / fine-tuned weights of one linear layer, [d_out, d_in]
+ *   B         = sign(W_f - W_b) in {-1,+1}^(d_out x d_in), stored one bit per entry
+ *   v         per-axis FP16 scale: one entry per output feature ("row" mode, length d_out)
+ *             or one per input feature ("col" mode, length d_in)
+ *   W_hat     = v (.) B + W_b                                                    (Eq. 1)
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller; nothing is copied from or
+ *     to the host.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on that stream and the call returns without synchronising; outputs are
+ *     valid once the stream reaches that point.
+ *   - The library allocates nothing and keeps no state between calls.
+ *   - Matrices are dense row-major: W[o, i] at W + o*d_in + i, X[m, i] at X + m*d_in + i,
+ *     Y[m, o] at Y + m*d_out + o.
+ *   - Bit layout: entry (o, i) is bit (i % 32) of the uint32 B_packed[o * (d_in/32) + i/32];
+ *     bit 1 means B = +1, bit 0 means B = -1 (consecutive input indices share a word, as the
+ *     paper's "1 bit along the input axis").  sign(0) is +1: the bit is !(W_f < W_b).
+ *   - d_in must be a multiple of 32 (PDELTA_ESHAPE otherwise).  Every pointer must be 16-byte
+ *     aligned (PDELTA_EALIGN).  v is always FP16 (Implementation remarks of the paper).
+ *   - Return value: a pdelta_status.  All argument checks happen on the host before any HIP
+ *     call, so they work without a GPU.  Nothing throws or aborts.  On an error return no
+ *     kernel has been launched.  Inputs are never written.  Outputs must not alias inputs
+ *     except where stated (pdelta_patch in place).
+ *   - NaN / Inf inputs are outside the contract.
+ */
+#ifndef PDELTA_H
+#define PDELTA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PDELTA_F16 = 0,  /* IEEE binary16 */
+    PDELTA_BF16 = 1, /* bfloat16 */
+    PDELTA_F32 = 2   /* IEEE binary32; accepted for Y only */
+} pdelta_dtype;
+
+typedef enum {
+    PDELTA_ROW = 0, /* v has d_out entries: W_hat[o,i] = W_b[o,i] + v[o] * B[o,i] */
+    PDELTA_COL = 1  /* v has d_in  entries: W_hat[o,i] = W_b[o,i] + v[i] * B[o,i] */
+} pdelta_axis;
+
+typedef enum {
+    PDELTA_OK = 0,
+    PDELTA_EINVAL = -1,     /* null pointer, non-positive dimension, bad axis, aliasing */
+    PDELTA_ESHAPE = -2,     /* d_in is not a multiple of 32, or a dimension is too large */
+    PDELTA_EALIGN = -3,     /* a pointer is not 16-byte aligned */
+    PDELTA_EDTYPE = -4,     /* dtype code not accepted by this entry point */
+    PDELTA_EWORKSPACE = -5, /* workspace missing or smaller than pdelta_pack_workspace_bytes */
+    PDELTA_EHIP = -6        /* a kernel launch failed; hipGetLastError has been consumed */
+} pdelta_status;
+
+/* Bytes of device scratch pdelta_pack needs for these dimensions (partial sums of |dW| per
+ * row and per column).  Returns 0 for non-positive dimensions. */
+size_t pdelta_pack_workspace_bytes(int64_t d_out, int64_t d_in);
+
+/*
+ * Offline companion: sign + bit-pack + per-axis scale initialisation.
+ *   B      = sign(W_f - W_b)                            (Section 2, definition of B)
+ *   Pack   : one bit per entry along the input axis     (per-layer compression algorithm,
+ *                                                        step "B <- Pack(sign(dW)^T)")
+ *   v_row[o] = mean_i |W_f[o,i] - W_b[o,i]|,  v_col[i] = mean_o |W_f[o,i] - W_b[o,i]|
+ *            (same algorithm, initial values of the Row and Col scale vectors), each the
+ *            exact mean rounded once to FP16 (nearest-even).
+ * Arguments
+ *   W_f, W_b   in   [d_out, d_in], dtype w_dtype (PDELTA_F16 or PDELTA_BF16)
+ *   B_packed   out  [d_out, d_in/32] uint32
+ *   v_row      out  FP16 [d_out], may be NULL
+ *   v_col      out  FP16 [d_in],  may be NULL
+ *   workspace  scratch, >= pdelta_pack_workspace_bytes(d_out, d_in) bytes, 16-byte aligned;
+ *              contents on entry are ignored, contents on exit are unspecified
+ * Exactness: for FP16 inputs the sums are accumulated as 64-bit integers in units of 2^-24,
+ * so the result does not depend on the order of accumulation and is bit-reproducible; it
+ * equals the fp64 reference bit for bit while each sum of |dW| stays below 2^29.  For BF16
+ * inputs sums are accumulated in fp64 (exact whenever all |dW| are multiples of a common
+ * 2^-q and the sum stays below 2^(53-q); otherwise within one FP16 ulp of the exact mean).
+ * d_out and d_in may each be at most 2^22.
+ */
+int pdelta_pack(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, int w_dtype,
+                uint32_t* B_packed, uint16_t* v_row, uint16_t* v_col,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Delta linear layer, row mode (Eq. 1 with v in R^(1 x d_out), then the layer forward
+ * Y = X W_hat^T), evaluated without forming W_hat in memory:
+ *   Y[m,o] = sum_i X[m,i] * W_b[o,i]  +  v_row[o] * sum_i X[m,i] * B[o,i]
+ * Arguments
+ *   X        in   [M, d_in],     dtype x_dtype (PDELTA_F16 or PDELTA_BF16)
+ *   W_b      in   [d_out, d_in], same dtype as X
+ *   B_packed in   [d_out, d_in/32] uint32
+ *   v_row    in   FP16 [d_out]
+ *   Y        out  [M, d_out], dtype y_dtype (PDELTA_F16, PDELTA_BF16 or PDELTA_F32)
+ * Products of the 16-bit operands are accumulated in fp32; Y is rounded to y_dtype once
+ * (nearest-even).  M = 0 is a no-op that returns PDELTA_OK (X and Y may then be NULL).  No
+ * bias term (the paper leaves biases untouched, Limitations section).
+ */
+int pdelta_linear_row(const void* X, const void* W_b, const uint32_t* B_packed,
+                      const uint16_t* v_row, void* Y, int64_t M, int64_t d_out, int64_t d_in,
+                      int x_dtype, int y_dtype, void* stream);
+
+/*
+ * Delta linear layer, column mode (Eq. 1 with v in R^(d_in x 1)):
+ *   Y[m,o] = sum_i X[m,i] * W_b[o,i]  +  sum_i (X[m,i] * v_col[i]) * B[o,i]
+ * Arguments as pdelta_linear_row, with v_col FP16 [d_in].
+ */
+int pdelta_linear_col(const void* X, const void* W_b, const uint32_t* B_packed,
+                      const uint16_t* v_col, void* Y, int64_t M, int64_t d_out, int64_t d_in,
+                      int x_dtype, int y_dtype, void* stream);
+
+/*
+ * Merge the delta into the weights (Eq. 1; the paper's deployed path adds all residual terms
+ * once, Limitations section, and applies a saved delta module by module, algorithm "Model-wide
+ * application from a saved delta file"):
+ *   W_out[o,i] = round_to_w_dtype( W_b[o,i] + v[o or i] * B[o,i] )
+ * The sum is formed exactly and rounded once (nearest-even).
+ * Arguments
+ *   W_b      in   [d_out, d_in], dtype w_dtype (PDELTA_F16 or PDELTA_BF16)
+ *   B_packed in   [d_out, d_in/32] uint32
+ *   v        in   FP16, [d_out] if axis == PDELTA_ROW, [d_in] if axis == PDELTA_COL
+ *   W_out    out  [d_out, d_in], dtype w_dtype; may be the same pointer as W_b (in place),
+ *                 must not overlap it otherwise
+ * With W_b = 0 and v = 1 the result is exactly +-1: the unpacked B.
+ */
+int pdelta_patch(const void* W_b, const uint32_t* B_packed, const uint16_t* v, int axis,
+                 void* W_out, int64_t d_out, int64_t d_in, int w_dtype, void* stream);
+
+/* Static, human-readable name of a pdelta_status value. */
+const char* pdelta_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PDELTA_H */

@@ -1,0 +1,164 @@
+// C ABI of the pdelta library (see include/pdelta.h): argument validation on the host, then
+// dispatch to the kernel families.  No allocation, no synchronisation, no state.
+#include "pdelta.h"
+
+#include <stdlib.h>
+#include <string.h>
+
+#include "pdelta_host.h"
+
+namespace pdelta {
+
+int tune_value(const char* key, int fallback)
+{
+    const char* env = getenv("PDELTA_TUNE");
+    if (env == nullptr) return fallback;
+    const size_t klen = strlen(key);
+    for (const char* p = env; *p != '\0';) {
+        if (strncmp(p, key, klen) == 0 && p[klen] == '=') return atoi(p + klen + 1);
+        const char* comma = strchr(p, ',');
+        if (comma == nullptr) break;
+        p = comma + 1;
+    }
+    return fallback;
+}
+
+namespace {
+
+constexpr int64_t kMaxDim = (int64_t)1 << 22;      // per-axis limit of pack's exact sums
+constexpr int64_t kMaxTokens = (int64_t)1 << 23;
+
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+// true when [a, a+na) and [b, b+nb) share a byte
+inline bool overlaps(const void* a, size_t na, const void* b, size_t nb)
+{
+    const uintptr_t pa = (uintptr_t)a, pb = (uintptr_t)b;
+    return pa < pb + nb && pb < pa + na;
+}
+
+inline bool is_w_dtype(int d) { return d == PDELTA_F16 || d == PDELTA_BF16; }
+inline bool is_y_dtype(int d) { return d == PDELTA_F16 || d == PDELTA_BF16 || d == PDELTA_F32; }
+
+int check_dims(int64_t d_out, int64_t d_in)
+{
+    if (d_out <= 0 || d_in <= 0) return PDELTA_EINVAL;
+    if (d_in % 32 != 0 || d_out > kMaxDim || d_in > kMaxDim) return PDELTA_ESHAPE;
+    return PDELTA_OK;
+}
+
+int linear_common(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
+                  void* Y, int64_t M, int64_t d_out, int64_t d_in, int x_dtype, int y_dtype,
+                  int axis, void* stream)
+{
+    if (W_b == nullptr || B_packed == nullptr || v == nullptr) return PDELTA_EINVAL;
+    if (M < 0) return PDELTA_EINVAL;
+    if (M > 0 && (X == nullptr || Y == nullptr)) return PDELTA_EINVAL;   // an empty batch has no X, Y
+    if (const int rc = check_dims(d_out, d_in)) return rc;
+    if (M > kMaxTokens) return PDELTA_ESHAPE;
+    if (!is_w_dtype(x_dtype) || !is_y_dtype(y_dtype)) return PDELTA_EDTYPE;
+    if (misaligned(X) || misaligned(W_b) || misaligned(B_packed) || misaligned(v) || misaligned(Y))
+        return PDELTA_EALIGN;
+    if (M == 0) return PDELTA_OK;
+    const size_t y_bytes = (size_t)M * d_out * (y_dtype == PDELTA_F32 ? 4 : 2);
+    const size_t v_bytes = (size_t)(axis == PDELTA_ROW ? d_out : d_in) * 2;
+    if (overlaps(Y, y_bytes, X, (size_t)M * d_in * 2) ||
+        overlaps(Y, y_bytes, W_b, (size_t)d_out * d_in * 2) ||
+        overlaps(Y, y_bytes, B_packed, (size_t)d_out * d_in / 8) || overlaps(Y, y_bytes, v, v_bytes))
+        return PDELTA_EINVAL;
+
+    hipStream_t s = (hipStream_t)stream;
+    const int rc = M <= pdelta::kSkinnyMaxM
+                       ? pdelta::launch_linear_skinny(x_dtype, y_dtype, axis, X, W_b, B_packed, v, Y, M,
+                                                      d_out, d_in, s)
+                       : pdelta::launch_linear_gemm(x_dtype, y_dtype, axis, X, W_b, B_packed, v, Y, M,
+                                                    d_out, d_in, s);
+    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+}
+
+}  // namespace
+}  // namespace pdelta
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+size_t pdelta_pack_workspace_bytes(int64_t d_out, int64_t d_in)
+{
+    if (d_out <= 0 || d_in <= 0) return 0;
+    return (size_t)(d_out + d_in) * 8;
+}
+
+int pdelta_pack(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, int w_dtype,
+                uint32_t* B_packed, uint16_t* v_row, uint16_t* v_col, void* workspace,
+                size_t workspace_bytes, void* stream)
+{
+    using namespace pdelta;
+    if (W_f == nullptr || W_b == nullptr || B_packed == nullptr) return PDELTA_EINVAL;
+    if (const int rc = check_dims(d_out, d_in)) return rc;
+    if (!is_w_dtype(w_dtype)) return PDELTA_EDTYPE;
+    const bool want_scales = v_row != nullptr || v_col != nullptr;
+    if (want_scales && (workspace == nullptr || workspace_bytes < pdelta_pack_workspace_bytes(d_out, d_in)))
+        return PDELTA_EWORKSPACE;
+    if (misaligned(W_f) || misaligned(W_b) || misaligned(B_packed) || misaligned(v_row) ||
+        misaligned(v_col) || (want_scales && misaligned(workspace)))
+        return PDELTA_EALIGN;
+    const size_t w_bytes = (size_t)d_out * d_in * 2, b_bytes = (size_t)d_out * d_in / 8;
+    if (overlaps(B_packed, b_bytes, W_f, w_bytes) || overlaps(B_packed, b_bytes, W_b, w_bytes))
+        return PDELTA_EINVAL;
+    const int rc = launch_pack_dispatch(w_dtype, W_f, W_b, d_out, d_in, B_packed, v_row, v_col,
+                                        workspace, (hipStream_t)stream);
+    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+}
+
+int pdelta_linear_row(const void* X, const void* W_b, const uint32_t* B_packed,
+                      const uint16_t* v_row, void* Y, int64_t M, int64_t d_out, int64_t d_in,
+                      int x_dtype, int y_dtype, void* stream)
+{
+    return pdelta::linear_common(X, W_b, B_packed, v_row, Y, M, d_out, d_in, x_dtype, y_dtype,
+                                 PDELTA_ROW, stream);
+}
+
+int pdelta_linear_col(const void* X, const void* W_b, const uint32_t* B_packed,
+                      const uint16_t* v_col, void* Y, int64_t M, int64_t d_out, int64_t d_in,
+                      int x_dtype, int y_dtype, void* stream)
+{
+    return pdelta::linear_common(X, W_b, B_packed, v_col, Y, M, d_out, d_in, x_dtype, y_dtype,
+                                 PDELTA_COL, stream);
+}
+
+int pdelta_patch(const void* W_b, const uint32_t* B_packed, const uint16_t* v, int axis,
+                 void* W_out, int64_t d_out, int64_t d_in, int w_dtype, void* stream)
+{
+    using namespace pdelta;
+    if (W_b == nullptr || B_packed == nullptr || v == nullptr || W_out == nullptr) return PDELTA_EINVAL;
+    if (axis != PDELTA_ROW && axis != PDELTA_COL) return PDELTA_EINVAL;
+    if (const int rc = check_dims(d_out, d_in)) return rc;
+    if (!is_w_dtype(w_dtype)) return PDELTA_EDTYPE;
+    if (misaligned(W_b) || misaligned(B_packed) || misaligned(v) || misaligned(W_out))
+        return PDELTA_EALIGN;
+    const size_t w_bytes = (size_t)d_out * d_in * 2;
+    if (W_out != W_b && overlaps(W_out, w_bytes, W_b, w_bytes)) return PDELTA_EINVAL;
+    if (overlaps(W_out, w_bytes, B_packed, w_bytes / 16) ||
+        overlaps(W_out, w_bytes, v, (size_t)(axis == PDELTA_ROW ? d_out : d_in) * 2))
+        return PDELTA_EINVAL;
+    const int rc = launch_patch_dispatch(w_dtype, axis, W_b, B_packed, v, W_out, d_out, d_in,
+                                         (hipStream_t)stream);
+    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+}
+
+const char* pdelta_status_string(int status)
+{
+    switch (status) {
+        case PDELTA_OK: return "PDELTA_OK";
+        case PDELTA_EINVAL: return "PDELTA_EINVAL: null pointer, bad dimension or axis, or aliasing";
+        case PDELTA_ESHAPE: return "PDELTA_ESHAPE: d_in not a multiple of 32 or dimension too large";
+        case PDELTA_EALIGN: return "PDELTA_EALIGN: pointer not 16-byte aligned";
+        case PDELTA_EDTYPE: return "PDELTA_EDTYPE: dtype not accepted here";
+        case PDELTA_EWORKSPACE: return "PDELTA_EWORKSPACE: workspace missing or too small";
+        case PDELTA_EHIP: return "PDELTA_EHIP: kernel launch failed";
+        default: return "unknown pdelta status";
+    }
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

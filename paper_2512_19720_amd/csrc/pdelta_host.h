@@ -1,0 +1,33 @@
+// Host-side launch functions, one per kernel family.  Each returns 0 when every launch was
+// accepted and -1 otherwise.  Arguments have been validated by the C-ABI layer (pdelta_api.hip).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pdelta {
+
+int launch_pack_dispatch(int w_dtype, const void* W_f, const void* W_b, int64_t d_out,
+                         int64_t d_in, uint32_t* B_packed, uint16_t* v_row, uint16_t* v_col,
+                         void* workspace, hipStream_t stream);
+
+int launch_patch_dispatch(int w_dtype, int axis, const void* W_b, const uint32_t* B_packed,
+                          const uint16_t* v, void* W_out, int64_t d_out, int64_t d_in,
+                          hipStream_t stream);
+
+// Decode-shaped layer (few tokens): HBM-bound streaming kernel.  M <= kSkinnyMaxM.
+constexpr int kSkinnyMaxM = 64;
+int launch_linear_skinny(int x_dtype, int y_dtype, int axis, const void* X, const void* W_b,
+                         const uint32_t* B_packed, const uint16_t* v, void* Y, int64_t M,
+                         int64_t d_out, int64_t d_in, hipStream_t stream);
+
+// Prefill-shaped layer (many tokens): MFMA tile kernel.
+int launch_linear_gemm(int x_dtype, int y_dtype, int axis, const void* X, const void* W_b,
+                       const uint32_t* B_packed, const uint16_t* v, void* Y, int64_t M,
+                       int64_t d_out, int64_t d_in, hipStream_t stream);
+
+// Integer tuning knobs read once from the environment variable PDELTA_TUNE
+// ("key=value,key=value"); returns `fallback` when the key is absent.
+int tune_value(const char* key, int fallback);
+
+}  // namespace pdelta

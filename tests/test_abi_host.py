@@ -1,0 +1,121 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function
+the header declares, and turns every invalid argument into its error code before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_19720_amd import binding as pd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+A = 0x10000          # a fake, 16-byte aligned, non-null device address (never dereferenced)
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "pdelta.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pdelta_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    names = declared_functions()
+    assert {"pdelta_pack", "pdelta_linear_row", "pdelta_linear_col", "pdelta_patch",
+            "pdelta_pack_workspace_bytes", "pdelta_status_string"} <= set(names)
+    L = pd.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings():
+    L = pd.lib()
+    for code in range(0, -7, -1):
+        s = L.pdelta_status_string(code).decode()
+        assert s.startswith("PDELTA_")
+    assert "unknown" in L.pdelta_status_string(5).decode()
+
+
+def test_workspace_bytes():
+    assert pd.pdelta_pack_workspace_bytes(4096, 11008) == 8 * (4096 + 11008)
+    assert pd.pdelta_pack_workspace_bytes(0, 32) == 0
+    assert pd.pdelta_pack_workspace_bytes(32, -1) == 0
+
+
+def call_linear(fn="pdelta_linear_row", X=A, W=A + 0x1000000, B=A + 0x2000000, v=A + 0x3000000,
+                Y=A + 0x4000000, M=4, d_out=64, d_in=128, xdt=pd.F16, ydt=pd.F16):
+    return getattr(pd.lib(), fn)(X, W, B, v, Y, M, d_out, d_in, xdt, ydt, None)
+
+
+@pytest.mark.parametrize("fn", ["pdelta_linear_row", "pdelta_linear_col"])
+def test_linear_argument_errors(fn):
+    for null in ("X", "W", "B", "v", "Y"):
+        assert call_linear(fn, **{null: None}) == pd.EINVAL
+    assert call_linear(fn, M=-1) == pd.EINVAL
+    assert call_linear(fn, d_out=0) == pd.EINVAL
+    assert call_linear(fn, d_in=0) == pd.EINVAL
+    assert call_linear(fn, d_in=100) == pd.ESHAPE
+    assert call_linear(fn, d_in=48) == pd.ESHAPE
+    assert call_linear(fn, d_out=(1 << 22) + 1) == pd.ESHAPE
+    assert call_linear(fn, xdt=pd.F32) == pd.EDTYPE
+    assert call_linear(fn, xdt=7) == pd.EDTYPE
+    assert call_linear(fn, ydt=3) == pd.EDTYPE
+    for name in ("X", "W", "B", "v", "Y"):
+        assert call_linear(fn, **{name: A + 0x5000000 + 8}) == pd.EALIGN
+    # Y overlapping an input
+    assert call_linear(fn, Y=A + 0x1000000) == pd.EINVAL
+    assert call_linear(fn, Y=A + 16) == pd.EINVAL                      # inside X
+    # an empty batch is a no-op, decided on the host
+    assert call_linear(fn, M=0) == pd.OK
+    assert call_linear(fn, M=0, X=None, Y=None) == pd.OK
+    assert call_linear(fn, M=0, d_in=33) == pd.ESHAPE                  # still validated
+
+
+def call_pack(Wf=A, Wb=A + 0x1000000, d_out=64, d_in=128, dt=pd.F16, B=A + 0x2000000,
+              vr=A + 0x3000000, vc=A + 0x3100000, ws=A + 0x4000000, wsb=1 << 20):
+    return pd.lib().pdelta_pack(Wf, Wb, d_out, d_in, dt, B, vr, vc, ws, wsb, None)
+
+
+def test_pack_argument_errors():
+    for null in ("Wf", "Wb", "B"):
+        assert call_pack(**{null: None}) == pd.EINVAL
+    assert call_pack(d_out=-3) == pd.EINVAL
+    assert call_pack(d_in=65) == pd.ESHAPE
+    assert call_pack(d_in=(1 << 22) + 32) == pd.ESHAPE
+    assert call_pack(dt=pd.F32) == pd.EDTYPE
+    assert call_pack(ws=None) == pd.EWORKSPACE
+    assert call_pack(wsb=8 * (64 + 128) - 1) == pd.EWORKSPACE
+    assert call_pack(ws=A + 0x4000000 + 4) == pd.EALIGN
+    assert call_pack(Wf=A + 2) == pd.EALIGN
+    assert call_pack(vr=A + 0x3000000 + 2) == pd.EALIGN
+    assert call_pack(B=A + 32) == pd.EINVAL                             # B_packed inside W_f
+
+
+def call_patch(W=A, B=A + 0x1000000, v=A + 0x2000000, axis=pd.ROW, out=A + 0x3000000, d_out=64,
+               d_in=128, dt=pd.F16):
+    return pd.lib().pdelta_patch(W, B, v, axis, out, d_out, d_in, dt, None)
+
+
+def test_patch_argument_errors():
+    for null in ("W", "B", "v", "out"):
+        assert call_patch(**{null: None}) == pd.EINVAL
+    assert call_patch(axis=2) == pd.EINVAL
+    assert call_patch(axis=-1) == pd.EINVAL
+    assert call_patch(d_in=16) == pd.ESHAPE
+    assert call_patch(dt=pd.F32) == pd.EDTYPE
+    assert call_patch(out=A + 0x3000000 + 6) == pd.EALIGN
+    assert call_patch(out=A + 64) == pd.EINVAL                          # partial overlap with W_b
+    assert call_patch(out=A + 0x1000000) == pd.EINVAL                   # W_out on top of B_packed
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    W = torch.zeros((32, 32), dtype=torch.float16)
+    with pytest.raises(ValueError):
+        pd.pdelta_patch(W, torch.zeros((32, 1), dtype=torch.int32), torch.zeros(32, dtype=torch.float16), pd.ROW)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(pd, "_lib", None)
+    monkeypatch.setattr(pd, "_LIB_PATH", "/nonexistent/libpdelta.so")
+    with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
+        pd.lib()

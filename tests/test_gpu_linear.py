@@ -1,0 +1,118 @@
+"""GPU parity of pdelta_linear_row / pdelta_linear_col against the CPU oracle.
+
+Small and medium shapes are compared element by element against the full fp64 product; the
+prefill shapes of the benchmark are compared on sampled outputs (one fp64 dot product each).
+The tolerance rule is stated in parity_util.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pdelta_oracle as orc
+from paper_2512_19720_amd import binding as pd
+from paper_2512_19720_amd import synth
+from parity_util import DEV, check_y, f16_dev, gpu_linear, make_case, to_dev, words_dev, words_host
+
+pytestmark = pytest.mark.gpu
+
+TORCH_Y = {pd.F16: torch.float16, pd.BF16: torch.bfloat16, pd.F32: torch.float32}
+
+
+def run_both_axes(L, y_dtypes, what):
+    d = L["d"]
+    for axis, v_bits, v_dev in ((orc.ROW, L["v_row"], d["v_row"]), (orc.COL, L["v_col"], d["v_col"])):
+        ref = orc.linear(L["X"], L["W_b"], L["B"], v_bits, axis, L["dtype"])
+        for yd in y_dtypes:
+            Y = gpu_linear(axis, d["X"], d["W_b"], d["B"], v_dev, TORCH_Y[yd])
+            check_y(Y, ref, f"{what} axis={axis} y_dtype={yd}")
+
+
+def test_config0_single_layer_256x512_batch4():
+    L = make_case(256, 512, 4, synth.F16, "row", synth.seed_for(0))
+    # the GPU pack of the same delta must hand the linear layer the same B and v
+    B, v_row, _ = pd.pdelta_pack(L["d"]["dW"], torch.zeros_like(L["d"]["dW"]))
+    torch.cuda.synchronize()
+    assert np.array_equal(words_host(B), L["B"])
+    assert np.array_equal(synth.torch_to_bits(v_row), L["v_row"])
+    run_both_axes(L, (pd.F16, pd.F32, pd.BF16), "config0")
+
+
+@pytest.mark.parametrize("M", [1, 16])
+@pytest.mark.parametrize("sigma_axis", ["row", "col"])
+def test_config1_decode_4096x4096(M, sigma_axis):
+    L = make_case(4096, 4096, M, synth.F16, sigma_axis, synth.seed_for(1, M + (100 if sigma_axis == "col" else 0)))
+    run_both_axes(L, (pd.F16, pd.F32), f"config1 M={M} sigma={sigma_axis}")
+
+
+# ragged everything: d_out % 16 != 0, d_in % 128 != 0, token counts around the 16-token tiles
+@pytest.mark.parametrize("M", [1, 2, 3, 15, 16, 17, 31, 33, 48, 49, 64])
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_decode_path_ragged_shapes(M, dtype):
+    for d_out, d_in in ((100, 160), (16, 32), (7, 1056)):
+        L = make_case(d_out, d_in, M, dtype, "row", synth.seed_for(1, 1000 + M + d_out))
+        run_both_axes(L, (pd.F32, pd.F16 if dtype == synth.F16 else pd.BF16), f"decode {d_out}x{d_in} M={M} dt={dtype}")
+
+
+@pytest.mark.parametrize("shape", [(4096, 11008), (11008, 4096)])
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_decode_stack_shapes_batch1(shape, dtype):
+    for sigma_axis in ("row", "col"):
+        L = make_case(shape[0], shape[1], 1, dtype, sigma_axis, synth.seed_for(3, shape[0] % 97))
+        run_both_axes(L, (pd.F32, pd.F16 if dtype == synth.F16 else pd.BF16), f"stack {shape} {sigma_axis} dt={dtype}")
+
+
+# prefill path: M > 64.  Ragged M, d_out and d_in around the 128 x 128 x 64 tile
+@pytest.mark.parametrize("M,d_out,d_in", [(65, 128, 64), (200, 100, 96), (256, 300, 160), (129, 257, 1024),
+                                          (128, 128, 32), (1000, 384, 512)])
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_prefill_path_small_and_ragged(M, d_out, d_in, dtype):
+    L = make_case(d_out, d_in, M, dtype, "row", synth.seed_for(2, M + d_out + d_in))
+    run_both_axes(L, (pd.F32, pd.F16 if dtype == synth.F16 else pd.BF16), f"prefill {M}x{d_out}x{d_in} dt={dtype}")
+
+
+def test_zero_scale_gives_the_base_layer_and_constant_scale_makes_modes_agree():
+    L = make_case(192, 256, 8, synth.F16, "row", 42)
+    d = L["d"]
+    base = L["X"].view(np.float16).astype(np.float64) @ L["W_b"].view(np.float16).astype(np.float64).T
+    Y0 = gpu_linear(orc.ROW, d["X"], d["W_b"], d["B"], torch.zeros(192, dtype=torch.float16, device=DEV), torch.float32)
+    check_y(Y0, base, "v=0")
+    c = torch.full((256,), 0.0017, dtype=torch.float16, device=DEV)
+    Yr = gpu_linear(orc.ROW, d["X"], d["W_b"], d["B"], c[:192].contiguous(), torch.float32)
+    Yc = gpu_linear(orc.COL, d["X"], d["W_b"], d["B"], c, torch.float32)
+    # col mode rounds each X*c product to fp16 (rel. 2^-11) before the +-1 contraction
+    assert torch.allclose(Yr, Yc, rtol=0, atol=1e-4)
+
+
+def test_empty_batch_is_a_no_op():
+    L = make_case(64, 128, 1, synth.F16, "row", 1)
+    d = L["d"]
+    Y = pd.pdelta_linear_row(d["X"][:0].contiguous(), d["W_b"], d["B"], d["v_row"])
+    assert Y.shape == (0, 64)
+
+
+@pytest.mark.parametrize("shape", synth.PREFILL_SHAPES)
+def test_config2_prefill_full_size_sampled_outputs(shape):
+    """bf16, M = 2048, the benchmark's launch configuration; 600 sampled outputs, each an fp64 dot
+    product by the oracle, plus whole rows and columns of the output tile grid's corners."""
+    d_out, d_in = shape
+    M = 2048
+    seed = synth.seed_for(2, d_out % 1000 + d_in % 1000)
+    Ld = synth.layer_device(d_out, d_in, synth.BF16, "row", seed, DEV)
+    X = synth.x_device(M, d_in, synth.BF16, seed + 1, DEV)
+    B, v_row, _ = pd.pdelta_pack(Ld["dW"], torch.zeros_like(Ld["dW"]))
+    rng = np.random.default_rng(seed)
+    m_idx = np.concatenate([rng.integers(0, M, 560), [0, M - 1, 0, M - 1], np.full(36, 1027)])
+    o_idx = np.concatenate([rng.integers(0, d_out, 560), [0, 0, d_out - 1, d_out - 1], rng.integers(0, d_out, 36)])
+    rows = np.unique(o_idx)
+    # oracle side: pack and multiply only the sampled rows of the layer
+    Wb_rows = synth.torch_to_bits(Ld["W_b"][rows])
+    dW_rows = synth.torch_to_bits(Ld["dW"][rows])
+    Bo, vo, _ = orc.pack(dW_rows, np.zeros_like(dW_rows), orc.BF16, want_col=False)
+    assert np.array_equal(words_host(B[rows]), Bo)
+    assert np.array_equal(synth.torch_to_bits(v_row[rows]), vo)
+    Xh = synth.torch_to_bits(X)
+    ref = orc.linear_at(Xh, Wb_rows, Bo, vo, orc.ROW, m_idx, np.searchsorted(rows, o_idx), orc.BF16)
+    for yd in (torch.float32, torch.bfloat16):
+        Y = gpu_linear(orc.ROW, X, Ld["W_b"], B, v_row, yd)
+        got = Y[torch.from_numpy(m_idx).to(DEV), torch.from_numpy(o_idx).to(DEV)].reshape(1, -1)
+        check_y(got, ref.reshape(1, -1), f"config2 {shape} y={yd}")
