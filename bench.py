@@ -1,0 +1,280 @@
+#!/usr/bin/env python3
+"""Benchmark of the pdelta hot path on one MI355X.
+
+One timed "step" = the decode workload of the 4096 x 4096 fp16 layer: row and column mode at
+batch 1 and batch 16 (four launches), each launch on a different (W_b, B, v) buffer set so that
+it streams from HBM rather than from the 256 MB memory-side cache.  `value` is the effective
+bandwidth of those K steps: algorithmic bytes (every weight, sign word, scale, X and Y once)
+divided by wall time between two events on the launching stream.  The same process then times,
+each with its own events, the other workloads of the path (prefill GEMM shapes, the 224-linear
+decode stack, the offline pack of that stack, the in-place patch) and the CPU oracle on a
+bounded sample; they are reported as extra objects on the same JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--skip prefill,stack,pack,patch,cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 / fp16
+METRIC = "delta-linear decode GB/s + prefill TFLOP/s, % of MI355X HBM/MFMA roofline"
+
+
+def decode_bytes(d_out: int, d_in: int, M: int, axis: str) -> int:
+    """Algorithmic HBM bytes of one decode launch: W_b, packed signs, v, X in, Y out (fp16)."""
+    v_len = d_out if axis == "row" else d_in
+    return 2 * d_out * d_in + d_out * d_in // 8 + 2 * v_len + 2 * M * d_in + 2 * M * d_out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--skip", type=str, default="")
+    ap.add_argument("--sets", type=int, default=24, help="rotating buffer sets for the decode layer")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+    skip = set(s for s in args.skip.split(",") if s)
+
+    import numpy as np
+    import torch
+    from paper_2512_19720_amd import binding as pd
+    from paper_2512_19720_amd import synth
+
+    pd.lib()                                   # fail loudly if the HIP library is not built
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    f16 = torch.float16
+
+    def timed(fn, iters: int) -> float:
+        """Milliseconds for `iters` calls of fn between two events on the current stream."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    def make_layer(d_out, d_in, dtype, sigma_axis, seed):
+        """W_b plus pack(dW, 0) -> (W_b, B, v_row, v_col); the delta itself is dropped."""
+        L = synth.layer_device(d_out, d_in, dtype, sigma_axis, seed, dev)
+        B, v_row, v_col = pd.pdelta_pack(L["dW"], torch.zeros_like(L["dW"]))
+        return L["W_b"], B, v_row, v_col
+
+    # ---------------- decode: d_out = d_in = 4096, fp16, row/col x batch 1/16 ------------------
+    N = K = 4096
+    sets = [make_layer(N, K, synth.F16, "row" if s % 2 == 0 else "col", synth.seed_for(1, s))
+            for s in range(args.sets)]
+    X1 = synth.x_device(1, K, synth.F16, synth.seed_for(1, 900), dev)
+    X16 = synth.x_device(16, K, synth.F16, synth.seed_for(1, 901), dev)
+    Y1 = torch.empty((1, N), dtype=f16, device=dev)
+    Y16 = torch.empty((16, N), dtype=f16, device=dev)
+    cases = [("row", 1), ("col", 1), ("row", 16), ("col", 16)]
+    rot = [0]
+
+    def decode_call(axis, M):
+        W_b, B, v_row, v_col = sets[rot[0] % len(sets)]
+        rot[0] += 1
+        X, Y = (X1, Y1) if M == 1 else (X16, Y16)
+        if axis == "row":
+            pd.pdelta_linear_row(X, W_b, B, v_row, out=Y)
+        else:
+            pd.pdelta_linear_col(X, W_b, B, v_col, out=Y)
+
+    def decode_step():
+        for axis, M in cases:
+            decode_call(axis, M)
+
+    step_bytes = sum(decode_bytes(N, K, M, axis) for axis, M in cases)
+    for _ in range(args.warmup):
+        decode_step()
+    torch.cuda.synchronize()
+    t_wall0 = time.perf_counter()
+    ms_total = timed(decode_step, args.steps)
+    wall_s = time.perf_counter() - t_wall0
+    ms_per_step = ms_total / args.steps
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    per_case = {}
+    for axis, M in cases:
+        ms = timed(lambda: decode_call(axis, M), 200) / 200
+        b = decode_bytes(N, K, M, axis)
+        per_case[f"{axis}_M{M}"] = {"us": round(ms * 1e3, 3), "GB/s": round(b / ms / 1e6, 1),
+                                    "frac_hbm": round(b / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    hot = timed(lambda: pd.pdelta_linear_row(X1, sets[0][0], sets[0][1], sets[0][2], out=Y1), 200) / 200
+    per_case["row_M1_cache_hot_single_buffer"] = {"us": round(hot * 1e3, 3)}
+
+    launches = args.steps * len(cases)
+    avg_launch_us = ms_total * 1e3 / launches
+    roofline = {"bound": "hbm", "kernel": "linear_skinny_kernel (decode, 4096x4096 fp16)",
+                "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(value / HBM_PEAK_GBS, 4),
+                "bytes_per_launch": step_bytes // len(cases),
+                "avg_launch_us": round(avg_launch_us, 3), "traffic": None}
+
+    out = {
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "config1: decode GEMV d_out=d_in=4096 fp16, row+col x M in {1,16}, "
+                               f"{args.sets} rotating buffer sets ({args.sets * 35.7:.0f} MB)",
+                   "bytes_per_step": step_bytes},
+        "roofline": roofline, "decode_cases": per_case, "wall_s_timed_region": round(wall_s, 4),
+    }
+    del sets
+    torch.cuda.empty_cache()
+
+    # ---------------- prefill: bf16, M = 2048, three MLP shapes, row scales --------------------
+    if "prefill" not in skip:
+        pre = {}
+        tot_flop, tot_ms = 0.0, 0.0
+        M = 2048
+        for d_out, d_in in synth.PREFILL_SHAPES:
+            W_b, B, v_row, _ = make_layer(d_out, d_in, synth.BF16, "row", synth.seed_for(2, d_out % 1000))
+            X = synth.x_device(M, d_in, synth.BF16, synth.seed_for(2, 7), dev)
+            Y = torch.empty((M, d_out), dtype=torch.bfloat16, device=dev)
+            fn = lambda: pd.pdelta_linear_row(X, W_b, B, v_row, out=Y)
+            timed(fn, 3)
+            ms = timed(fn, 20) / 20
+            flop = 2.0 * M * d_out * d_in
+            pre[f"{d_out}x{d_in}"] = {"us": round(ms * 1e3, 1), "TFLOP/s": round(flop / ms / 1e9, 1),
+                                      "frac_mfma": round(flop / ms / 1e9 / MFMA_PEAK_TFLOPS, 4)}
+            tot_flop += flop
+            tot_ms += ms
+            del W_b, B, v_row, X, Y
+        agg = tot_flop / tot_ms / 1e9
+        out["prefill"] = {"workload": "config2: bf16 X [2048, d_in], row scales, bf16 Y", "shapes": pre,
+                          "TFLOP/s": round(agg, 1)}
+        out["roofline_prefill"] = {"bound": "mfma", "kernel": "linear_gemm_kernel (prefill, bf16 in, fp16 MFMA)",
+                                   "achieved": round(agg, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": round(agg / MFMA_PEAK_TFLOPS, 4), "traffic": None}
+        torch.cuda.empty_cache()
+
+    # ---------------- stack: 224 linears of a 7B-shaped model, batch 1 -------------------------
+    layers = None
+    if "stack" not in skip or "pack" not in skip or "patch" not in skip:
+        shapes = synth.stack_shapes()
+        layers = []
+        for li, (name, d_out, d_in, axis) in enumerate(shapes):
+            W_b, B, v_row, v_col = make_layer(d_out, d_in, synth.F16, axis, synth.seed_for(3, li))
+            layers.append((d_out, d_in, axis, W_b, B, v_row if axis == "row" else v_col))
+        Xs = {4096: synth.x_device(1, 4096, synth.F16, synth.seed_for(3, 900), dev),
+              11008: synth.x_device(1, 11008, synth.F16, synth.seed_for(3, 901), dev)}
+        Ys = [torch.empty((1, l[0]), dtype=f16, device=dev) for l in layers]
+        torch.cuda.synchronize()
+
+    if "stack" not in skip:
+        def stack_pass():
+            for (d_out, d_in, axis, W_b, B, v), Y in zip(layers, Ys):
+                if axis == "row":
+                    pd.pdelta_linear_row(Xs[d_in], W_b, B, v, out=Y)
+                else:
+                    pd.pdelta_linear_col(Xs[d_in], W_b, B, v, out=Y)
+
+        stack_bytes = sum(decode_bytes(l[0], l[1], 1, l[2]) for l in layers)
+        timed(stack_pass, 2)
+        ms = timed(stack_pass, 10) / 10
+        res = {"workload": "config3: 224 linears (32 x q,k,v,o,gate,up,down), fp16, M=1, row/col by block",
+               "bytes_per_token": stack_bytes, "ms_per_token": round(ms, 4),
+               "tokens/s": round(1e3 / ms, 1), "GB/s": round(stack_bytes / ms / 1e6, 1),
+               "frac_hbm": round(stack_bytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        # same launches replayed from a HIP graph (no host launch gaps)
+        try:
+            g = torch.cuda.CUDAGraph()
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(s):
+                stack_pass()
+            torch.cuda.current_stream().wait_stream(s)
+            with torch.cuda.graph(g):
+                stack_pass()
+            timed(g.replay, 2)
+            msg = timed(g.replay, 10) / 10
+            res["graph"] = {"ms_per_token": round(msg, 4), "tokens/s": round(1e3 / msg, 1),
+                            "frac_hbm": round(stack_bytes / msg / 1e6 / HBM_PEAK_GBS, 4)}
+        except Exception as exc:  # graph capture is an extra; the stream figure stands on its own
+            res["graph"] = {"error": str(exc)[:200]}
+        out["stack"] = res
+
+    # ---------------- pack: offline pass over the same 224 shapes ------------------------------
+    if "pack" not in skip:
+        # W_f = round(W_b + dW) per layer with 5 % exact zeros in dW; 13 GB more of HBM
+        Wfs = []
+        for li, (d_out, d_in, axis, W_b, _, _) in enumerate(layers):
+            L = synth.layer_device(d_out, d_in, synth.F16, "row", synth.seed_for(4, li), dev, zero_frac=0.05)
+            Wfs.append((W_b.float() + L["dW"].float()).to(f16))
+            del L
+        outs = [(torch.empty((l[0], l[1] // 32), dtype=torch.int32, device=dev),
+                 torch.empty(l[0], dtype=f16, device=dev), torch.empty(l[1], dtype=f16, device=dev))
+                for l in layers]
+        ws = torch.empty(pd.pdelta_pack_workspace_bytes(11008, 11008), dtype=torch.uint8, device=dev)
+
+        def pack_pass():
+            for l, Wf, o in zip(layers, Wfs, outs):
+                pd.pdelta_pack(Wf, l[3], out=o, workspace=ws)
+
+        pack_bytes = sum(4 * l[0] * l[1] + l[0] * l[1] // 8 + 2 * (l[0] + l[1]) for l in layers)
+        timed(pack_pass, 1)
+        ms = timed(pack_pass, 5) / 5
+        out["pack"] = {"workload": "config4: pdelta_pack over the 224 layers, fp16, 5% zero deltas, v_row + v_col",
+                       "bytes": pack_bytes, "ms": round(ms, 3), "GB/s": round(pack_bytes / ms / 1e6, 1),
+                       "frac_hbm": round(pack_bytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        del Wfs, outs
+        torch.cuda.empty_cache()
+
+    # ---------------- patch: merge the delta into all 224 layers, out of place -----------------
+    if "patch" not in skip:
+        big = torch.empty(11008 * 4096, dtype=f16, device=dev)
+
+        def patch_pass():
+            for (d_out, d_in, axis, W_b, B, v) in layers:
+                pd.pdelta_patch(W_b, B, v, pd.ROW if axis == "row" else pd.COL, out=big[: d_out * d_in].view(d_out, d_in))
+
+        patch_bytes = sum(4 * l[0] * l[1] + l[0] * l[1] // 8 for l in layers)
+        timed(patch_pass, 1)
+        ms = timed(patch_pass, 5) / 5
+        out["patch"] = {"workload": "pdelta_patch over the 224 layers (read W_b + signs, write W_hat), fp16",
+                        "bytes": patch_bytes, "ms": round(ms, 3), "GB/s": round(patch_bytes / ms / 1e6, 1),
+                        "frac_hbm": round(patch_bytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    layers = None
+    torch.cuda.empty_cache()
+
+    # ---------------- CPU oracle on a bounded sample of the decode workload --------------------
+    if "cpu" not in skip:
+        from oracle import pdelta_oracle as orc
+        L = synth.layer_host(N, K, 16, synth.F16, "row", synth.seed_for(1, 0))
+        Bo, vr, vc = orc.pack(L["dW"], np.zeros_like(L["dW"]))
+        reps = 3
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            for axis, M in cases:
+                orc.linear(L["X"][:M], L["W_b"], Bo, vr if axis == "row" else vc,
+                           orc.ROW if axis == "row" else orc.COL)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(reps * step_bytes / dt / 1e9, 4), "unit": "GB/s",
+                               "cores": orc.threads(), "kind": "oracle",
+                               "sample": f"{reps} passes of the same 4-launch decode step on one buffer set "
+                                         f"(fp64, dense W_hat rebuilt per call), {dt:.1f} s"}
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
