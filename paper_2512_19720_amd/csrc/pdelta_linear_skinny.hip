@@ -90,7 +90,7 @@ __device__ __forceinline__ void skinny_load(SkinnyStep<MT, AXIS>& r, const uint1
         r.w[j] = live ? *(const uint4v*)(wrow + k) : zero;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-            r.x[mt][j] = (live && xrow[mt] != nullptr) ? *(const uint4v*)(xrow[mt] + k) : zero;
+            r.x[mt][j] = live ? *(const uint4v*)(xrow[mt] + k) : zero;
         if constexpr (AXIS == 1) r.vc[j] = live ? *(const uint4v*)(vcol + k) : zero;
     }
 }
@@ -121,7 +121,8 @@ __device__ __forceinline__ void skinny_compute(const SkinnyStep<MT, AXIS>& r, in
 }
 
 // grid.x = ceil(d_out / 16); block = WAVES * 64; dynamic LDS = WAVES * MT * 256 floats.
-template <int XDT, int AXIS, int MT, int WAVES, bool K128>
+// DEPTH steps per wave are kept in flight (a ring of register buffers).
+template <int XDT, int AXIS, int MT, int WAVES, int DEPTH, bool K128>
 __global__ void __launch_bounds__(WAVES * 64)
 linear_skinny_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
                      const uint32_t* __restrict__ B_packed, const uint16_t* __restrict__ v,
@@ -140,9 +141,16 @@ linear_skinny_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict_
     const uint16_t* xrow[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const int t = mt * 16 + n;                    // A operand: lane % 16 is the token
-        xrow[mt] = t < M ? X + (int64_t)t * K + g * 8 : nullptr;
+        // A operand: lane % 16 is the token.  Tokens past the batch re-read the last real one:
+        // MFMA output rows are independent and those rows are never stored, and a load that
+        // every lane performs keeps the loop free of divergent branches and of the waits on
+        // all outstanding loads that come with them.
+        const int t = min(mt * 16 + n, M - 1);
+        xrow[mt] = X + (int64_t)t * K + g * 8;
     }
+
+    float vr = 1.0f;                                  // row scale: fetched with the first loads
+    if constexpr (AXIS == 0) vr = f16_bits_to_f32(v[o]);
 
     float4v accb[MT], accs[MT];
 #pragma unroll
@@ -151,21 +159,41 @@ linear_skinny_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict_
         accs[mt] = (float4v){0.f, 0.f, 0.f, 0.f};
     }
 
+    // This wave owns steps wave, wave + WAVES, ...  The ring keeps DEPTH of them in flight.  In
+    // the steady-state loop every load is unconditional: a load behind a branch makes the
+    // compiler wait for all outstanding loads at the join, which would serialise the ring.
     const int nsteps = (K + 127) >> 7;
-    SkinnyStep<MT, AXIS> cur, nxt;
-    int s = wave;
-    if (s < nsteps) skinny_load<MT, AXIS, K128>(cur, wrow, brow, xrow, vcol, s << 7, K);
-    while (s < nsteps) {
-        const int s2 = s + WAVES;
-        if (s2 < nsteps) skinny_load<MT, AXIS, K128>(nxt, wrow, brow, xrow, vcol, s2 << 7, K);
-        skinny_compute<XDT, MT, AXIS>(cur, g, accb, accs);
-        cur = nxt;
-        s = s2;
+    const int mine = nsteps > wave ? (nsteps - wave + WAVES - 1) / WAVES : 0;
+    SkinnyStep<MT, AXIS> buf[DEPTH];
+    auto kb_of = [&](int i) { return (wave + i * WAVES) << 7; };
+    if (mine >= DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) skinny_load<MT, AXIS, K128>(buf[d], wrow, brow, xrow, vcol, kb_of(d), K);
+        int i = 0;
+        for (; i + 2 * DEPTH <= mine; i += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                skinny_compute<XDT, MT, AXIS>(buf[d], g, accb, accs);
+                skinny_load<MT, AXIS, K128>(buf[d], wrow, brow, xrow, vcol, kb_of(i + DEPTH + d), K);
+            }
+        }
+        const int rest = mine - i - DEPTH;            // loads still to issue, 0 <= rest < DEPTH
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            skinny_compute<XDT, MT, AXIS>(buf[d], g, accb, accs);
+            if (d < rest) skinny_load<MT, AXIS, K128>(buf[d], wrow, brow, xrow, vcol, kb_of(i + DEPTH + d), K);
+        }
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            if (d < rest) skinny_compute<XDT, MT, AXIS>(buf[d], g, accb, accs);
+    } else {
+        for (int i = 0; i < mine; ++i) {              // fewer steps than the ring is deep
+            skinny_load<MT, AXIS, K128>(buf[0], wrow, brow, xrow, vcol, kb_of(i), K);
+            skinny_compute<XDT, MT, AXIS>(buf[0], g, accb, accs);
+        }
     }
 
     // Accumulator layout: element r of lane (n, g) is token g*4 + r, output row n0 + n.
-    float vr = 1.0f;
-    if constexpr (AXIS == 0) vr = f16_bits_to_f32(v[o]);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -189,14 +217,229 @@ linear_skinny_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict_
     }
 }
 
-template <int XDT, int AXIS, int MT, int WAVES, bool K128>
+// ---- staged variant (M <= 16, d_in % 128 == 0, slabs fit in LDS) ---------------------------
+// What the plain kernel above loads besides W_b is small but awkward: the sign words of a step
+// are a 16-byte piece from each of 16 rows, and at one token X is 64 useful bytes per load
+// instruction.  Here the workgroup copies its whole sign slab (16 rows x d_in/8 bytes, one
+// contiguous region of B_packed) into LDS with coalesced 16-byte loads while the first W_b
+// loads are already in flight, and, when the batch is small enough, X as well (in column mode
+// together with fp16(X * v_col), computed once).  The steady-state loop then issues global
+// loads for W_b only and reads everything else from LDS.
+template <int AXIS, bool STAGE_X>
+struct StagedStep {
+    uint4v w[4];
+    uint4v x[STAGE_X ? 1 : 4];
+    uint4v vc[(!STAGE_X && AXIS == 1) ? 4 : 1];
+};
+
+template <int XDT, int AXIS, int WAVES, int DEPTH, bool STAGE_X>
+__global__ void __launch_bounds__(WAVES * 64)
+linear_skinny_staged_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
+                            const uint32_t* __restrict__ B_packed, const uint16_t* __restrict__ v,
+                            void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int K = d_in;
+    const int wpr = K >> 5;                           // sign words per row
+    const int spr = wpr + 4;                          // LDS row stride in words: rows 16 B apart in banks
+    const int xpr = K + 8;                            // LDS row stride of X in halves
+    float* red = (float*)smem;                                        // [WAVES][4][64]
+    uint32_t* s_sign = (uint32_t*)(smem + WAVES * 1024);              // [16][spr]
+    uint16_t* s_x = (uint16_t*)(s_sign + 16 * spr);                   // [M][xpr]      (STAGE_X)
+    uint16_t* s_xv = s_x + (STAGE_X ? M * xpr : 0);                   // [M][xpr]      (STAGE_X, col)
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, g = lane >> 4;
+    const int n0 = blockIdx.x * 16;
+    const int o = min(n0 + n, d_out - 1);
+
+    const uint16_t* wrow = W_b + (int64_t)o * K + g * 8;
+    const int tok = min(n, M - 1);                    // A operand: lane % 16 = token (clamped, see above)
+    const uint16_t* xrow = X + (int64_t)tok * K + g * 8;
+    const uint16_t* vcol = v + g * 8;
+
+    auto load = [&](StagedStep<AXIS, STAGE_X>& r, int kb) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            r.w[j] = *(const uint4v*)(wrow + kb + j * 32);
+            if constexpr (!STAGE_X) {
+                r.x[j] = *(const uint4v*)(xrow + kb + j * 32);
+                if constexpr (AXIS == 1) r.vc[j] = *(const uint4v*)(vcol + kb + j * 32);
+            }
+        }
+    };
+
+    const int nsteps = K >> 7;
+    const int mine = nsteps > wave ? (nsteps - wave + WAVES - 1) / WAVES : 0;   // steps of this wave
+    auto kb_of = [&](int i) { return (wave + i * WAVES) << 7; };
+    StagedStep<AXIS, STAGE_X> buf[DEPTH];
+    const bool ring = mine >= DEPTH;                  // wave-uniform
+    if (ring) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) load(buf[d], kb_of(d));
+    }
+    float vr = 1.0f;
+    if constexpr (AXIS == 0) vr = f16_bits_to_f32(v[o]);
+
+    // stage the sign slab (and X) while those loads fly
+    {
+        const int upr = wpr >> 2;                     // 16-byte units per sign row
+        for (int i = tid; i < 16 * upr; i += WAVES * 64) {
+            const int row = i / upr, u = i - row * upr;
+            const int src_row = min(n0 + row, d_out - 1);
+            *(uint4v*)(s_sign + row * spr + u * 4) =
+                *(const uint4v*)(B_packed + (int64_t)src_row * wpr + u * 4);
+        }
+        if constexpr (STAGE_X) {
+            const int upt = K >> 3;                   // 16-byte units per token
+            for (int i = tid; i < M * upt; i += WAVES * 64) {
+                const int t = i / upt, u = i - t * upt;
+                const uint4v xv = *(const uint4v*)(X + (int64_t)t * K + u * 8);
+                *(uint4v*)(s_x + t * xpr + u * 8) = xv;
+                if constexpr (AXIS == 1)
+                    *(uint4v*)(s_xv + t * xpr + u * 8) = scale_x<XDT>(xv, *(const uint4v*)(v + u * 8));
+            }
+        }
+    }
+    __syncthreads();
+
+    float4v accb = {0.f, 0.f, 0.f, 0.f}, accs = {0.f, 0.f, 0.f, 0.f};
+    const uint32_t* my_sign = s_sign + n * spr;
+    const uint16_t* my_x = s_x + tok * xpr + g * 8;
+    const uint16_t* my_xv = s_xv + tok * xpr + g * 8;
+
+    auto compute = [&](const StagedStep<AXIS, STAGE_X>& r, int kb) {
+        const uint4v sw = *(const uint4v*)(my_sign + (kb >> 5));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t byte = (sw[j] >> (g * 8)) & 0xFFu;
+            uint4v xa, xs;
+            if constexpr (STAGE_X) {
+                xa = *(const uint4v*)(my_x + kb + j * 32);
+                if constexpr (AXIS == 1) xs = *(const uint4v*)(my_xv + kb + j * 32);
+            } else {
+                xa = r.x[j];
+                if constexpr (AXIS == 1) xs = scale_x<XDT>(xa, r.vc[j]);
+            }
+            accb = mfma16<XDT>(xa, r.w[j], accb);
+            if constexpr (AXIS == 0) accs = mfma16<XDT>(xa, expand_signs<XDT>(byte), accs);
+            else accs = mfma16<kF16>(xs, expand_signs<kF16>(byte), accs);
+        }
+    };
+
+    if (ring) {
+        int i = 0;
+        for (; i + 2 * DEPTH <= mine; i += DEPTH) {   // steady state: unconditional loads only
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                compute(buf[d], kb_of(i + d));
+                load(buf[d], kb_of(i + DEPTH + d));
+            }
+        }
+        const int rest = mine - i - DEPTH;            // loads still to issue, 0 <= rest < DEPTH
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            compute(buf[d], kb_of(i + d));
+            if (d < rest) load(buf[d], kb_of(i + DEPTH + d));
+        }
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            if (d < rest) compute(buf[d], kb_of(i + DEPTH + d));
+    } else {
+        for (int i = 0; i < mine; ++i) {
+            load(buf[0], kb_of(i));
+            compute(buf[0], kb_of(i));
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[(wave * 4 + r) * 64 + lane] = accb[r] + vr * accs[r];
+    __syncthreads();
+    for (int idx = tid; idx < 256; idx += WAVES * 64) {
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) sum += red[w * 256 + idx];
+        const int ln = idx & 63, r = idx >> 6;
+        const int t = (ln >> 4) * 4 + r;
+        const int oo = n0 + (ln & 15);
+        if (t < M && oo < d_out) {
+            const int64_t yi = (int64_t)t * d_out + oo;
+            if (y_dtype == kF32) store_y<kF32>(Y, yi, sum);
+            else if (y_dtype == kBF16) store_y<kBF16>(Y, yi, sum);
+            else store_y<kF16>(Y, yi, sum);
+        }
+    }
+}
+
+constexpr size_t kStagedLdsLimit = 96 * 1024;
+
+// LDS bytes of the staged kernel, or 0 when the slabs do not fit.
+static size_t staged_lds_bytes(int waves, int axis, bool stage_x, int64_t M, int64_t K)
+{
+    size_t bytes = (size_t)waves * 1024 + (size_t)16 * (K / 32 + 4) * 4;
+    if (stage_x) bytes += (size_t)M * (K + 8) * 2 * (axis == 1 ? 2 : 1);
+    return bytes <= kStagedLdsLimit ? bytes : 0;
+}
+
+template <int XDT, int AXIS, int WAVES, int DEPTH, bool STAGE_X>
+static int launch_staged(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
+                         void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype, size_t lds,
+                         hipStream_t stream)
+{
+    const dim3 grid((unsigned)((d_out + 15) / 16));
+    auto kernel = linear_skinny_staged_kernel<XDT, AXIS, WAVES, DEPTH, STAGE_X>;
+    if (lds > 48 * 1024) {   // above the default dynamic-LDS limit the kernel has to opt in
+        if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)kStagedLdsLimit) != hipSuccess)
+            return -1;
+    }
+    hipLaunchKernelGGL(kernel, grid, dim3(WAVES * 64), lds, stream, (const uint16_t*)X,
+                       (const uint16_t*)W_b, B_packed, v, Y, (int)M, (int)d_out, (int)d_in, y_dtype);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Returns 1 if the staged kernel does not apply, else the launch result (0 / -1).
+template <int XDT, int AXIS>
+static int try_staged(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
+                      void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
+                      hipStream_t stream)
+{
+    if (M > 16 || d_in % 128 != 0 || tune_value("skinny_staged", 1) == 0) return 1;
+    // Measured on MI355X: 8 waves with 2 steps in flight each is the best general choice; when a
+    // layer is wide (d_in >= 8192) but has few workgroups (<= 2 per CU) 16 waves fill the CU better.
+    const bool wide_few = d_in >= 8192 && (d_out + 15) / 16 <= 512;
+    const int waves = tune_value("stg_waves", wide_few ? 16 : 8);
+    const int depth = tune_value("stg_depth", 2);
+    const bool want_x = tune_value("stg_x", 1) != 0;
+    size_t lds = want_x ? staged_lds_bytes(waves, AXIS, true, M, d_in) : 0;
+    const bool stage_x = lds != 0 && M * d_in <= 24576;
+    if (!stage_x) lds = staged_lds_bytes(waves, AXIS, false, M, d_in);
+    if (lds == 0) return 1;
+#define PDELTA_STG(WAVES, DEPTH)                                                                        \
+    return stage_x ? launch_staged<XDT, AXIS, WAVES, DEPTH, true>(X, W_b, B_packed, v, Y, M, d_out, d_in, \
+                                                                   y_dtype, lds, stream)                  \
+                   : launch_staged<XDT, AXIS, WAVES, DEPTH, false>(X, W_b, B_packed, v, Y, M, d_out, d_in, \
+                                                                    y_dtype, lds, stream)
+    if (waves == 4) {
+        if (depth == 8) PDELTA_STG(4, 8);
+        PDELTA_STG(4, 4);
+    }
+    if (waves == 16) PDELTA_STG(16, 2);
+    if (depth == 2) PDELTA_STG(8, 2);
+    if (depth == 6) PDELTA_STG(8, 6);
+    PDELTA_STG(8, 4);
+#undef PDELTA_STG
+}
+
+template <int XDT, int AXIS, int MT, int WAVES, int DEPTH, bool K128>
 static int launch_one(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
                       void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
                       hipStream_t stream)
 {
     const dim3 grid((unsigned)((d_out + 15) / 16));
     const size_t lds = (size_t)WAVES * MT * 256 * sizeof(float);
-    hipLaunchKernelGGL((linear_skinny_kernel<XDT, AXIS, MT, WAVES, K128>), grid, dim3(WAVES * 64), lds,
+    hipLaunchKernelGGL((linear_skinny_kernel<XDT, AXIS, MT, WAVES, DEPTH, K128>), grid, dim3(WAVES * 64), lds,
                        stream, (const uint16_t*)X, (const uint16_t*)W_b, B_packed, v, Y, (int)M,
                        (int)d_out, (int)d_in, y_dtype);
     return hipGetLastError() == hipSuccess ? 0 : -1;
@@ -207,20 +450,25 @@ static int launch_by_tokens(const void* X, const void* W_b, const uint32_t* B_pa
                             const uint16_t* v, void* Y, int64_t M, int64_t d_out, int64_t d_in,
                             int y_dtype, hipStream_t stream)
 {
-#define PDELTA_GO(MT, WAVES) \
-    return launch_one<XDT, AXIS, MT, WAVES, K128>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream)
+#define PDELTA_GO(MT, WAVES, DEPTH) \
+    return launch_one<XDT, AXIS, MT, WAVES, DEPTH, K128>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream)
     const int waves = tune_value("skinny_waves", 8);
+    const int depth = tune_value("skinny_depth", 2);
     if (M <= 16) {
-        if (waves == 4) PDELTA_GO(1, 4);
-        if (waves == 16) PDELTA_GO(1, 16);
-        PDELTA_GO(1, 8);
+        if (waves == 4) {
+            if (depth == 4) PDELTA_GO(1, 4, 4);
+            if (depth == 6) PDELTA_GO(1, 4, 6);
+            PDELTA_GO(1, 4, 2);
+        }
+        if (waves == 16) PDELTA_GO(1, 16, 2);
+        if (depth == 1) PDELTA_GO(1, 8, 1);
+        if (depth == 3) PDELTA_GO(1, 8, 3);
+        if (depth == 4) PDELTA_GO(1, 8, 4);
+        PDELTA_GO(1, 8, 2);
     }
-    if (M <= 32) {
-        if (waves == 4) PDELTA_GO(2, 4);
-        PDELTA_GO(2, 8);
-    }
-    if (M <= 48) PDELTA_GO(3, 8);
-    PDELTA_GO(4, 8);
+    if (M <= 32) PDELTA_GO(2, 8, 2);
+    if (M <= 48) PDELTA_GO(3, 8, 1);
+    PDELTA_GO(4, 8, 1);
 #undef PDELTA_GO
 }
 
@@ -229,6 +477,16 @@ int launch_linear_skinny(int x_dtype, int y_dtype, int axis, const void* X, cons
                          int64_t d_out, int64_t d_in, hipStream_t stream)
 {
     const bool k128 = d_in % 128 == 0;
+    {
+        int rc = 1;
+        if (x_dtype == kBF16)
+            rc = axis == 0 ? try_staged<kBF16, 0>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream)
+                           : try_staged<kBF16, 1>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
+        else
+            rc = axis == 0 ? try_staged<kF16, 0>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream)
+                           : try_staged<kF16, 1>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
+        if (rc != 1) return rc;
+    }
 #define PDELTA_SEL(XDT, AXIS)                                                                      \
     return k128 ? launch_by_tokens<XDT, AXIS, true>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream) \
                 : launch_by_tokens<XDT, AXIS, false>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream)
