@@ -6,22 +6,34 @@
 // [2^-14, 65504] (bf16 carries 8 significant bits, fp16 11) and is the reason for the stated
 // operand range of the prefill path.
 //
-// Tile: 128 tokens x 128 output rows x 64 inputs per step, 256 threads = 4 waves in a 2 x 2
-// arrangement, each wave 64 x 64 outputs as 2 x 2 MFMA 32x32x16 tiles.  Global loads for step
-// s+1 are in flight while step s is multiplied out of LDS.
+// Tile: BM tokens x 128 output rows x 64 inputs per step (BM = 256, or 128 for short batches),
+// WM x 2 waves (8 waves of 64 x 64 outputs for BM = 256), each wave's outputs as MFMA 32x32x16
+// tiles.  One LDS stage of (BM + 128) x 64 fp16 (rows padded to 144 bytes so that 16-byte
+// fragment reads of 16 consecutive rows touch all 64 banks once); the global loads of step s+1
+// are in flight while step s is multiplied, and two workgroups share a CU so that one
+// converts and stages while the other keeps the matrix cores busy.
+//
+// Workgroup -> tile map.  Hardware deals consecutive workgroups round-robin to the 8 XCDs, each
+// with its own L2.  Workgroup w therefore belongs to XCD x = w % 8; its x-local index j = w / 8
+// walks all token tiles of one output-row tile before moving to the next, and the output-row
+// tiles of XCD x are x, x + 8, x + 16, ...  The tiles resident on one XCD at a time then share
+// a few W_b panels and all advance through d_in together, so the live slice of X and W_b stays
+// inside that XCD's 4 MB L2.
+#include <type_traits>
+
 #include "pdelta_device.h"
 #include "pdelta_host.h"
 
 namespace pdelta {
 
-constexpr int kGemmBM = 128, kGemmBN = 128, kGemmBK = 64;
-constexpr int kGemmLDK = kGemmBK + 8;   // padded LDS row (halves): 144 B stride, conflict-free b128 reads
-constexpr int kGemmThreads = 256;
+constexpr int kGemmBN = 128, kGemmBK = 64;
+constexpr int kGemmLDK = kGemmBK + 8;   // padded LDS row in halves (144 bytes)
+constexpr int kXcds = 8;
 
 __device__ __forceinline__ uint32_t bf16pair_to_f16pair(uint32_t d) {
     const float lo = __builtin_bit_cast(float, d << 16);
     const float hi = __builtin_bit_cast(float, d & 0xFFFF0000u);
-    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+    return as_u32(__builtin_bit_cast(half2v, __builtin_amdgcn_cvt_pkrtz(lo, hi)));
 }
 
 template <int XDT>
@@ -29,140 +41,201 @@ __device__ __forceinline__ uint4v to_f16x8(uint4v a) {
     if constexpr (XDT == kBF16) {
         uint4v r;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) r[p] = bf16pair_to_f16pair(a[p]);
+        for (int p = 0; p < 4; ++p) {
+            const uint32_t ap = a[p];
+            r[p] = bf16pair_to_f16pair(ap);
+        }
         return r;
     } else {
         return a;
     }
 }
 
-// Eight fp16 weights + eight sign bits + packed scales -> eight fp16 values of W_hat.
-// vv[p] holds the fp16 scales of elements 2p (low half) and 2p+1 (high half).
-__device__ __forceinline__ uint4v apply_delta(uint4v w, uint32_t byte, uint4v vv) {
-    const uint32_t neg = ~byte;
+// Eight fp16 weights and eight "negate" bits (bit e set: element e gets -|v|, clear: +|v|) with
+// the packed magnitudes |v| of elements 2p (low half) and 2p+1 (high half) in vabs[p].
+// Row mode: |v| is one value per row and the sign of v is folded into the bits by the caller.
+__device__ __forceinline__ uint4v add_signed_scale(uint4v w, uint32_t negbits, uint4v vabs) {
     uint4v r;
+    negbits &= 0xFFu;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        const uint32_t t = neg >> (2 * p);
-        const uint32_t flip = ((t & 1u) << 15) | ((t & 2u) << 30);
-        const uint32_t wp = w[p], sv = vv[p] ^ flip;                            // sv = +-v
-        r[p] = as_u32(as_half2(wp) + as_half2(sv));                             // v_pk_add_f16
+        // bit 2p -> position 15, bit 2p+1 -> position 31; everything else is masked by the insert
+        const uint32_t spread = (negbits << (30 - 2 * p)) | (negbits << (15 - 2 * p));
+        const uint32_t va = vabs[p], wp = w[p];
+        const uint32_t sv = (spread & 0x80008000u) | (va & 0x7FFF7FFFu);        // v_bfi_b32
+        r[p] = as_u32(as_half2(wp) + as_half2(sv));                              // v_pk_add_f16
     }
     return r;
 }
 
-template <int XDT, int AXIS>
-__global__ void __launch_bounds__(kGemmThreads)
+// WM x 2 waves; a wave owns (BM / WM) tokens x 64 output rows.
+template <int XDT, int AXIS, int BM, int WM>
+__global__ void __launch_bounds__(WM * 128, (WM * 128) / 128)
 linear_gemm_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
                    const uint32_t* __restrict__ B_packed, const uint16_t* __restrict__ v,
-                   void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype)
+                   void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype, int m_tiles,
+                   int n_tiles)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[kGemmBM * kGemmLDK];
+    constexpr int THREADS = WM * 128;
+    constexpr int ROWS = THREADS / 8;    // tile rows covered by one staging pass
+    constexpr int FM = BM / WM / 32;     // 32-row MFMA tiles per wave along tokens
+    constexpr int FN = 2;                // ... along output rows (wave covers 64)
+    constexpr int XQ = BM / ROWS;        // 16-byte vectors of X per thread and step
+    constexpr int WQ = kGemmBN / ROWS;   // ... of W_b
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[BM * kGemmLDK];
     __shared__ __attribute__((aligned(16))) uint16_t Ws[kGemmBN * kGemmLDK];
+
+    // tile of this workgroup (see the map in the header comment)
+    const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+    const int tile_n = (local / m_tiles) * kXcds + xcd;
+    const int tile_m = local % m_tiles;
+    if (tile_n >= n_tiles) return;       // whole workgroup
+    const int n0 = tile_n * kGemmBN, m0 = tile_m * BM;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int n0 = blockIdx.x * kGemmBN;
-    const int m0 = blockIdx.y * kGemmBM;
     const int K = d_in;
-    const uint8_t* B_bytes = (const uint8_t*)B_packed;
+    constexpr int WROWS = BM / WM;       // tokens per wave
 
-    // staging role: thread covers 8 inputs (16 bytes) at column ld_c of rows ld_row + 32 q
+    // Staging role: the thread covers 8 inputs (16 bytes) at column ld_c of tile rows
+    // ld_row + ROWS q.  Addresses are a workgroup-uniform base that advances with the step plus a
+    // fixed 32-bit per-thread byte offset, so the loop spends no vector ALU work on them.  Rows
+    // past the end of X or W_b are clamped to the last real row: such rows only feed outputs
+    // that are never stored, and every load stays unconditional (a load behind a branch makes
+    // the compiler drain all outstanding loads at the join).
     const int ld_row = tid >> 3, ld_c = (tid & 7) * 8;
-
-    uint4v vrow[4];
-    if constexpr (AXIS == 0) {
+    const char* xbase = (const char*)(X + (int64_t)m0 * K);
+    const char* wbase = (const char*)(W_b + (int64_t)n0 * K);
+    const char* sbase = (const char*)B_packed + (((int64_t)n0 * K) >> 3);
+    uint32_t xoff[XQ], woff[WQ], soff[WQ];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int o = n0 + ld_row + 32 * q;
-            const uint32_t h = o < d_out ? v[o] : 0u;
-            const uint32_t hh = h | (h << 16);
-            vrow[q] = (uint4v){hh, hh, hh, hh};
+    for (int q = 0; q < XQ; ++q) {
+        const int row = min(m0 + ld_row + ROWS * q, M - 1) - m0;
+        xoff[q] = ((uint32_t)row * (uint32_t)K + (uint32_t)ld_c) * 2u;
+    }
+    uint32_t vabs_row[WQ];               // row mode: |v| of the thread's W rows, in both halves
+    uint32_t vneg_row[WQ];               // row mode: 0xFF if v < 0 (flips every sign bit)
+#pragma unroll
+    for (int q = 0; q < WQ; ++q) {
+        const int row = min(n0 + ld_row + ROWS * q, d_out - 1) - n0;
+        woff[q] = ((uint32_t)row * (uint32_t)K + (uint32_t)ld_c) * 2u;
+        soff[q] = (uint32_t)row * (uint32_t)(K >> 3) + (uint32_t)(tid & 7);
+        if constexpr (AXIS == 0) {
+            const uint32_t h = v[n0 + row];
+            const uint32_t a = h & 0x7FFFu, aa = a | (a << 16);
+            vabs_row[q] = aa;
+            vneg_row[q] = (h & 0x8000u) ? 0xFFu : 0u;
         }
     }
 
-    uint4v xg[4], wg[4], vcg;
-    uint32_t sb[4];
+    uint4v xg[XQ], wg[WQ], vcg;
+    uint32_t sb[WQ];
     const uint4v zero = {0, 0, 0, 0};
 
-    auto load_global = [&](int kb) {
-        const int col = kb + ld_c;
-        const bool col_ok = col < K;
+    // GUARD: the last, partial step of a d_in that is not a multiple of 64 (it is one of 32).
+    auto load_global = [&](int kb, auto guard) {
+        constexpr bool GUARD = decltype(guard)::value;
+        const bool col_ok = !GUARD || kb + ld_c < K;
+        const char* xb = xbase + (int64_t)kb * 2;
+        const char* wb = wbase + (int64_t)kb * 2;
+        const char* sp = sbase + (kb >> 3);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int tok = m0 + ld_row + 32 * q;
-            xg[q] = (col_ok && tok < M) ? *(const uint4v*)(X + (int64_t)tok * K + col) : zero;
-            const int o = n0 + ld_row + 32 * q;
-            if (col_ok && o < d_out) {
-                const int64_t off = (int64_t)o * K + col;
-                wg[q] = *(const uint4v*)(W_b + off);
-                sb[q] = B_bytes[off >> 3];
-            } else {
-                wg[q] = zero;
-                sb[q] = 0xFFu;
-            }
+        for (int q = 0; q < XQ; ++q) xg[q] = col_ok ? *(const uint4v*)(xb + xoff[q]) : zero;
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) {
+            wg[q] = col_ok ? *(const uint4v*)(wb + woff[q]) : zero;
+            sb[q] = col_ok ? (uint32_t) * (const uint8_t*)(sp + soff[q]) : 0xFFu;
         }
-        if constexpr (AXIS == 1) vcg = col_ok ? *(const uint4v*)(v + col) : zero;
+        if constexpr (AXIS == 1) vcg = col_ok ? *(const uint4v*)(v + kb + ld_c) : zero;
     };
 
     auto store_lds = [&]() {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int r = ld_row + 32 * q;
-            *(uint4v*)(Xs + r * kGemmLDK + ld_c) = to_f16x8<XDT>(xg[q]);
+        for (int q = 0; q < XQ; ++q)
+            *(uint4v*)(Xs + (ld_row + ROWS * q) * kGemmLDK + ld_c) = to_f16x8<XDT>(xg[q]);
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) {
             const uint4v w16 = to_f16x8<XDT>(wg[q]);
-            *(uint4v*)(Ws + r * kGemmLDK + ld_c) = apply_delta(w16, sb[q], AXIS == 0 ? vrow[q] : vcg);
+            uint4v what;
+            if constexpr (AXIS == 0) {
+                const uint32_t aa = vabs_row[q];
+                what = add_signed_scale(w16, ~sb[q] ^ vneg_row[q], (uint4v){aa, aa, aa, aa});
+            } else {
+                // per-input scales: fold each scale's own sign into its negate bit
+                uint32_t vsign = 0;
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const uint32_t vp = vcg[p];
+                    vsign |= ((vp >> 15) & 1u) << (2 * p) | ((vp >> 31) & 1u) << (2 * p + 1);
+                }
+                what = add_signed_scale(w16, ~sb[q] ^ vsign, vcg);
+            }
+            *(uint4v*)(Ws + (ld_row + ROWS * q) * kGemmLDK + ld_c) = what;
         }
     };
 
-    float16v acc[2][2];
+    float16v acc[FM][FN];
 #pragma unroll
-    for (int f = 0; f < 2; ++f)
+    for (int f = 0; f < FM; ++f)
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < FN; ++h)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[f][h][r] = 0.f;
 
     const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+    const uint16_t* a_base = Xs + (wm * WROWS + frag_row) * kGemmLDK + frag_k;
+    const uint16_t* b_base = Ws + (wn * 64 + frag_row) * kGemmLDK + frag_k;
 
-    load_global(0);
-    store_lds();
-    __syncthreads();
-    for (int kb = 0; kb < K; kb += kGemmBK) {
-        const bool more = kb + kGemmBK < K;
-        if (more) load_global(kb + kGemmBK);
+    auto multiply_stage = [&]() {
 #pragma unroll
         for (int ks = 0; ks < kGemmBK / 16; ++ks) {
-            half8 a[2], b[2];
+            half8 a[FM], b[FN];
 #pragma unroll
-            for (int f = 0; f < 2; ++f)
-                a[f] = *(const half8*)(Xs + (wm * 64 + f * 32 + frag_row) * kGemmLDK + ks * 16 + frag_k);
+            for (int f = 0; f < FM; ++f) a[f] = *(const half8*)(a_base + f * 32 * kGemmLDK + ks * 16);
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
-                b[h] = *(const half8*)(Ws + (wn * 64 + h * 32 + frag_row) * kGemmLDK + ks * 16 + frag_k);
+            for (int h = 0; h < FN; ++h) b[h] = *(const half8*)(b_base + h * 32 * kGemmLDK + ks * 16);
 #pragma unroll
-            for (int f = 0; f < 2; ++f)
+            for (int f = 0; f < FM; ++f)
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
+                for (int h = 0; h < FN; ++h)
                     acc[f][h] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[f], b[h], acc[f][h], 0, 0, 0);
         }
+    };
+
+    const int full_steps = K / kGemmBK;              // unguarded steps
+    const bool tail = (K % kGemmBK) != 0;            // then one more step of 32 inputs
+    if (full_steps > 0) load_global(0, std::false_type{});
+    else load_global(0, std::true_type{});
+    for (int i = 0; i + 1 < full_steps; ++i) {       // steady state: always another full step
+        store_lds();
         __syncthreads();
-        if (more) {
-            store_lds();
-            __syncthreads();
-        }
+        load_global((i + 1) * kGemmBK, std::false_type{});
+        multiply_stage();
+        __syncthreads();
+    }
+    if (full_steps > 0) {                            // last full step
+        store_lds();
+        __syncthreads();
+        if (tail) load_global(full_steps * kGemmBK, std::true_type{});
+        multiply_stage();
+        __syncthreads();
+    }
+    if (tail) {
+        store_lds();
+        __syncthreads();
+        multiply_stage();
     }
 
     // 32x32 accumulator: element r of lane l is row (r/4)*8 + (l/32)*4 + r%4, column l%32.
 #pragma unroll
-    for (int f = 0; f < 2; ++f)
+    for (int f = 0; f < FM; ++f)
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < FN; ++h) {
             const int o = n0 + wn * 64 + h * 32 + (lane & 31);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int tok = m0 + wm * 64 + f * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                const int tok = m0 + wm * WROWS + f * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
                 if (tok < M && o < d_out) {
                     const int64_t yi = (int64_t)tok * d_out + o;
                     const float val = acc[f][h][r];
@@ -174,16 +247,31 @@ linear_gemm_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ 
         }
 }
 
-template <int XDT, int AXIS>
+template <int XDT, int AXIS, int BM, int WM>
 static int launch_gemm(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
                        void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
                        hipStream_t stream)
 {
-    const dim3 grid((unsigned)((d_out + kGemmBN - 1) / kGemmBN), (unsigned)((M + kGemmBM - 1) / kGemmBM));
-    hipLaunchKernelGGL((linear_gemm_kernel<XDT, AXIS>), grid, dim3(kGemmThreads), 0, stream,
+    const int m_tiles = (int)((M + BM - 1) / BM);
+    const int n_tiles = (int)((d_out + kGemmBN - 1) / kGemmBN);
+    const int n_groups = (n_tiles + kXcds - 1) / kXcds;
+    const dim3 grid((unsigned)((int64_t)n_groups * kXcds * m_tiles));
+    hipLaunchKernelGGL((linear_gemm_kernel<XDT, AXIS, BM, WM>), grid, dim3(WM * 128), 0, stream,
                        (const uint16_t*)X, (const uint16_t*)W_b, B_packed, v, Y, (int)M, (int)d_out,
-                       (int)d_in, y_dtype);
+                       (int)d_in, y_dtype, m_tiles, n_tiles);
     return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+template <int XDT, int AXIS>
+static int launch_gemm_bm(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
+                          void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
+                          hipStream_t stream)
+{
+    if (M <= 128 || tune_value("gemm_bm", 256) == 128)
+        return launch_gemm<XDT, AXIS, 128, 2>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
+    if (tune_value("gemm_wm", 4) == 4)
+        return launch_gemm<XDT, AXIS, 256, 4>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
+    return launch_gemm<XDT, AXIS, 256, 2>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
 }
 
 int launch_linear_gemm(int x_dtype, int y_dtype, int axis, const void* X, const void* W_b,
@@ -191,10 +279,10 @@ int launch_linear_gemm(int x_dtype, int y_dtype, int axis, const void* X, const 
                        int64_t d_out, int64_t d_in, hipStream_t stream)
 {
     if (x_dtype == kBF16)
-        return axis == 0 ? launch_gemm<kBF16, 0>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream)
-                         : launch_gemm<kBF16, 1>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
-    return axis == 0 ? launch_gemm<kF16, 0>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream)
-                     : launch_gemm<kF16, 1>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
+        return axis == 0 ? launch_gemm_bm<kBF16, 0>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream)
+                         : launch_gemm_bm<kBF16, 1>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
+    return axis == 0 ? launch_gemm_bm<kF16, 0>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream)
+                     : launch_gemm_bm<kF16, 1>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
 }
 
 }  // namespace pdelta
