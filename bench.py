@@ -42,6 +42,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--skip", type=str, default="")
     ap.add_argument("--sets", type=int, default=24, help="rotating buffer sets for the decode layer")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB) so that "
+                         "a rocprofv3 --pmc run of this command has a kernel of known traffic in it")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -58,6 +61,15 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     f16 = torch.float16
+
+    if args.calibrate:
+        src = torch.ones(1 << 29, dtype=f16, device=dev)          # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)                            # one read + one write per element
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     def timed(fn, iters: int) -> float:
         """Milliseconds for `iters` calls of fn between two events on the current stream."""
@@ -119,13 +131,21 @@ def main() -> int:
     hot = timed(lambda: pd.pdelta_linear_row(X1, sets[0][0], sets[0][1], sets[0][2], out=Y1), 200) / 200
     per_case["row_M1_cache_hot_single_buffer"] = {"us": round(hot * 1e3, 3)}
 
+    # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by the
+    # plain-copy calibration); taken from the committed summary when it exists.
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "decode_4096x4096_pmc_traffic.md")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = int(float(line.split(":", 1)[1].split()[0]))
     launches = args.steps * len(cases)
     avg_launch_us = ms_total * 1e3 / launches
     roofline = {"bound": "hbm", "kernel": "linear_skinny_kernel (decode, 4096x4096 fp16)",
                 "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(value / HBM_PEAK_GBS, 4),
                 "bytes_per_launch": step_bytes // len(cases),
-                "avg_launch_us": round(avg_launch_us, 3), "traffic": None}
+                "avg_launch_us": round(avg_launch_us, 3), "traffic": traffic}
 
     out = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
