@@ -230,6 +230,16 @@ def main() -> int:
                             "frac_hbm": round(stack_bytes / msg / 1e6 / HBM_PEAK_GBS, 4)}
         except Exception as exc:  # graph capture is an extra; the stream figure stands on its own
             res["graph"] = {"error": str(exc)[:200]}
+        # the same 224 layers through the batched entry point: one launch instead of 224
+        ROW_COL = {"row": pd.ROW, "col": pd.COL}
+        plan = pd.pdelta_linear_batch_plan(
+            [(Xs[d_in], W_b, B, v, ROW_COL[axis], Y) for (d_out, d_in, axis, W_b, B, v), Y in zip(layers, Ys)])
+        timed(lambda: pd.pdelta_linear_batch(plan), 2)
+        msb = timed(lambda: pd.pdelta_linear_batch(plan), 10) / 10
+        res["batched"] = {"entry_point": "pdelta_linear_batch", "ms_per_token": round(msb, 4),
+                          "tokens/s": round(1e3 / msb, 1),
+                          "frac_hbm": round(stack_bytes / msb / 1e6 / HBM_PEAK_GBS, 4)}
+        del plan
         out["stack"] = res
 
     # ---------------- pack: offline pass over the same 224 shapes ------------------------------

@@ -132,6 +132,39 @@ int pdelta_linear_col(const void* X, const void* W_b, const uint32_t* B_packed,
 int pdelta_patch(const void* W_b, const uint32_t* B_packed, const uint16_t* v, int axis,
                  void* W_out, int64_t d_out, int64_t d_in, int w_dtype, void* stream);
 
+/*
+ * Several delta linear layers in one launch, for layers that do not depend on each other (the
+ * q/k/v or gate/up projections of one block, or many fine-tuned variants of one base served
+ * together, the setting the paper's introduction motivates).  Every layer computes exactly what
+ * pdelta_linear_row / pdelta_linear_col computes (Eq. 1 inside the layer forward); all layers
+ * share the batch size M and the dtypes, each has its own X, W_b, B_packed, v, Y, shape and axis.
+ *
+ * pdelta_layer describes one layer; all pointers are device pointers as above.
+ * pdelta_linear_batch_plan (host only, no HIP call) checks every descriptor of a HOST array as
+ * the single-layer entry points would and fills `first_block`.  The caller then copies the array
+ * to device memory and passes both copies: the host copy is read for validation and launch
+ * geometry, the device copy by the kernel.  Editing pointers later needs no new plan as long
+ * as shapes and axes stay the same (copy the array again).
+ * When the layers do not fit the batched decode kernel (M > 16, d_in not a multiple of 128, or
+ * operand slabs too large for LDS) the call launches them one by one in order, with the same
+ * results.  M = 0 or n_layers = 0 is a no-op.
+ */
+typedef struct pdelta_layer {
+    const void* X;            /* [M, d_in] */
+    const void* W_b;          /* [d_out, d_in] */
+    const uint32_t* B_packed; /* [d_out, d_in/32] */
+    const uint16_t* v;        /* FP16, [d_out] (row) or [d_in] (col) */
+    void* Y;                  /* out [M, d_out] */
+    int64_t d_out, d_in;
+    int32_t axis;             /* PDELTA_ROW or PDELTA_COL */
+    int32_t first_block;      /* filled by pdelta_linear_batch_plan */
+} pdelta_layer;
+
+int pdelta_linear_batch_plan(pdelta_layer* layers_host, int32_t n_layers);
+
+int pdelta_linear_batch(const pdelta_layer* layers_host, const pdelta_layer* layers_device,
+                        int32_t n_layers, int64_t M, int x_dtype, int y_dtype, void* stream);
+
 /* Static, human-readable name of a pdelta_status value. */
 const char* pdelta_status_string(int status);
 

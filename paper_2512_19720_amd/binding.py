@@ -26,6 +26,13 @@ class PdeltaError(RuntimeError):
         super().__init__(f"{where}: {lib().pdelta_status_string(status).decode()} ({status})")
 
 
+class Layer(ctypes.Structure):
+    """Mirror of the C struct ``pdelta_layer``."""
+    _fields_ = [("X", ctypes.c_void_p), ("W_b", ctypes.c_void_p), ("B_packed", ctypes.c_void_p),
+                ("v", ctypes.c_void_p), ("Y", ctypes.c_void_p), ("d_out", ctypes.c_int64),
+                ("d_in", ctypes.c_int64), ("axis", ctypes.c_int32), ("first_block", ctypes.c_int32)]
+
+
 def lib() -> ctypes.CDLL:
     """The loaded C library.  Raises if it has not been built (no fallback exists)."""
     global _lib
@@ -46,6 +53,10 @@ def lib() -> ctypes.CDLL:
             f.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, vp]
         L.pdelta_patch.restype = i32
         L.pdelta_patch.argtypes = [vp, vp, vp, i32, vp, i64, i64, i32, vp]
+        L.pdelta_linear_batch_plan.restype = i32
+        L.pdelta_linear_batch_plan.argtypes = [ctypes.POINTER(Layer), ctypes.c_int32]
+        L.pdelta_linear_batch.restype = i32
+        L.pdelta_linear_batch.argtypes = [ctypes.POINTER(Layer), vp, ctypes.c_int32, i64, i32, i32, vp]
         L.pdelta_status_string.restype = ctypes.c_char_p
         L.pdelta_status_string.argtypes = [i32]
         _lib = L
@@ -139,3 +150,56 @@ def pdelta_patch(W_b, B_packed, v, axis: int, out=None):
                             _dev(out, "W_out"), d_out, d_in, dtype_code(W_b.dtype), _stream())
     _check(rc, "pdelta_patch")
     return out
+
+
+class BatchPlan:
+    """Host and device copies of a planned ``pdelta_layer`` array plus the tensors they point to."""
+
+    def __init__(self, host, device, tensors, M, x_dtype, y_dtype):
+        self.host, self.device, self.tensors = host, device, tensors
+        self.M, self.x_dtype, self.y_dtype = M, x_dtype, y_dtype
+        self.Y = [t[4] for t in tensors]
+
+    def __len__(self):
+        return len(self.host)
+
+
+def pdelta_linear_batch_plan(layers, out_dtype=None) -> BatchPlan:
+    """Describe independent layers for one batched launch.
+
+    ``layers`` is a sequence of ``(X, W_b, B_packed, v, axis)`` or ``(X, W_b, B_packed, v, axis, Y)``
+    with one common batch size and dtype; missing outputs are allocated.  The descriptor array is
+    planned by the library on the host and copied to the GPU once.
+    """
+    layers = list(layers)
+    if not layers:
+        raise ValueError("no layers")
+    M, x_dtype = layers[0][0].shape[0], layers[0][0].dtype
+    host = (Layer * len(layers))()
+    tensors = []
+    for k, item in enumerate(layers):
+        X, W_b, B_packed, v, axis = item[:5]
+        Y = item[5] if len(item) > 5 else None
+        d_out, d_in = W_b.shape
+        if X.shape != (M, d_in) or X.dtype != x_dtype or W_b.dtype != x_dtype:
+            raise ValueError("layers of one batch share M and dtype; X and W_b must agree in d_in")
+        if Y is None:
+            Y = torch.empty((M, d_out), dtype=out_dtype or x_dtype, device=X.device)
+        host[k] = Layer(_dev(X, "X") or None, _dev(W_b, "W_b"), _dev(B_packed, "B_packed"), _dev(v, "v"),
+                        _dev(Y, "Y") or None, d_out, d_in, axis, 0)
+        tensors.append((X, W_b, B_packed, v, Y))
+    y_dtype = tensors[0][4].dtype
+    if any(t[4].dtype != y_dtype for t in tensors):
+        raise ValueError("layers of one batch share the output dtype")
+    _check(lib().pdelta_linear_batch_plan(host, len(layers)), "pdelta_linear_batch_plan")
+    raw = torch.frombuffer(bytearray(bytes(host)), dtype=torch.uint8)
+    device = raw.to(tensors[0][0].device)
+    return BatchPlan(host, device, tensors, M, dtype_code(x_dtype), dtype_code(y_dtype))
+
+
+def pdelta_linear_batch(plan: BatchPlan):
+    """Run every layer of the plan (one launch when the layers fit the batched decode kernel)."""
+    rc = lib().pdelta_linear_batch(plan.host, plan.device.data_ptr(), len(plan), plan.M, plan.x_dtype,
+                                   plan.y_dtype, _stream())
+    _check(rc, "pdelta_linear_batch")
+    return plan.Y

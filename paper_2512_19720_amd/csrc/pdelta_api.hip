@@ -47,11 +47,31 @@ int check_dims(int64_t d_out, int64_t d_in)
     return PDELTA_OK;
 }
 
+// Argument checks of one delta linear layer (no launch).
+int linear_check(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
+                 void* Y, int64_t M, int64_t d_out, int64_t d_in, int x_dtype, int y_dtype, int axis);
+
 int linear_common(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
                   void* Y, int64_t M, int64_t d_out, int64_t d_in, int x_dtype, int y_dtype,
                   int axis, void* stream)
 {
+    if (const int rc = linear_check(X, W_b, B_packed, v, Y, M, d_out, d_in, x_dtype, y_dtype, axis))
+        return rc;
+    if (M == 0) return PDELTA_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const int rc = M <= pdelta::kSkinnyMaxM
+                       ? pdelta::launch_linear_skinny(x_dtype, y_dtype, axis, X, W_b, B_packed, v, Y, M,
+                                                      d_out, d_in, s)
+                       : pdelta::launch_linear_gemm(x_dtype, y_dtype, axis, X, W_b, B_packed, v, Y, M,
+                                                    d_out, d_in, s);
+    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+}
+
+int linear_check(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
+                 void* Y, int64_t M, int64_t d_out, int64_t d_in, int x_dtype, int y_dtype, int axis)
+{
     if (W_b == nullptr || B_packed == nullptr || v == nullptr) return PDELTA_EINVAL;
+    if (axis != PDELTA_ROW && axis != PDELTA_COL) return PDELTA_EINVAL;
     if (M < 0) return PDELTA_EINVAL;
     if (M > 0 && (X == nullptr || Y == nullptr)) return PDELTA_EINVAL;   // an empty batch has no X, Y
     if (const int rc = check_dims(d_out, d_in)) return rc;
@@ -66,14 +86,7 @@ int linear_common(const void* X, const void* W_b, const uint32_t* B_packed, cons
         overlaps(Y, y_bytes, W_b, (size_t)d_out * d_in * 2) ||
         overlaps(Y, y_bytes, B_packed, (size_t)d_out * d_in / 8) || overlaps(Y, y_bytes, v, v_bytes))
         return PDELTA_EINVAL;
-
-    hipStream_t s = (hipStream_t)stream;
-    const int rc = M <= pdelta::kSkinnyMaxM
-                       ? pdelta::launch_linear_skinny(x_dtype, y_dtype, axis, X, W_b, B_packed, v, Y, M,
-                                                      d_out, d_in, s)
-                       : pdelta::launch_linear_gemm(x_dtype, y_dtype, axis, X, W_b, B_packed, v, Y, M,
-                                                    d_out, d_in, s);
-    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+    return PDELTA_OK;
 }
 
 }  // namespace
@@ -143,6 +156,56 @@ int pdelta_patch(const void* W_b, const uint32_t* B_packed, const uint16_t* v, i
         return PDELTA_EINVAL;
     const int rc = launch_patch_dispatch(w_dtype, axis, W_b, B_packed, v, W_out, d_out, d_in,
                                          (hipStream_t)stream);
+    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+}
+
+int pdelta_linear_batch_plan(pdelta_layer* layers_host, int32_t n_layers)
+{
+    if (n_layers < 0 || (n_layers > 0 && layers_host == nullptr)) return PDELTA_EINVAL;
+    int64_t first = 0;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        pdelta_layer& L = layers_host[l];
+        if (L.axis != PDELTA_ROW && L.axis != PDELTA_COL) return PDELTA_EINVAL;
+        if (const int rc = pdelta::check_dims(L.d_out, L.d_in)) return rc;
+        if (first > 0x7FFFFFFF) return PDELTA_ESHAPE;
+        L.first_block = (int32_t)first;
+        first += (L.d_out + 15) / 16;
+    }
+    return PDELTA_OK;
+}
+
+int pdelta_linear_batch(const pdelta_layer* layers_host, const pdelta_layer* layers_device,
+                        int32_t n_layers, int64_t M, int x_dtype, int y_dtype, void* stream)
+{
+    using namespace pdelta;
+    if (n_layers < 0 || M < 0) return PDELTA_EINVAL;
+    if (n_layers == 0) return PDELTA_OK;
+    if (layers_host == nullptr || layers_device == nullptr) return PDELTA_EINVAL;
+    if (misaligned(layers_device)) return PDELTA_EALIGN;
+    int64_t first = 0;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const pdelta_layer& L = layers_host[l];
+        if (const int rc = linear_check(L.X, L.W_b, L.B_packed, L.v, L.Y, M, L.d_out, L.d_in, x_dtype,
+                                        y_dtype, L.axis))
+            return rc;
+        if (L.first_block != (int32_t)first) return PDELTA_EINVAL;     // not planned, or edited
+        first += (L.d_out + 15) / 16;
+    }
+    if (M == 0) return PDELTA_OK;
+    hipStream_t s = (hipStream_t)stream;
+    int rc = M <= kSkinnyMaxM ? launch_linear_skinny_batch(x_dtype, y_dtype, layers_host, layers_device,
+                                                           n_layers, M, s)
+                              : 1;
+    if (rc == 1) {                                                      // layer by layer
+        rc = 0;
+        for (int32_t l = 0; l < n_layers && rc == 0; ++l) {
+            const pdelta_layer& L = layers_host[l];
+            rc = M <= kSkinnyMaxM ? launch_linear_skinny(x_dtype, y_dtype, L.axis, L.X, L.W_b, L.B_packed,
+                                                         L.v, L.Y, M, L.d_out, L.d_in, s)
+                                  : launch_linear_gemm(x_dtype, y_dtype, L.axis, L.X, L.W_b, L.B_packed,
+                                                       L.v, L.Y, M, L.d_out, L.d_in, s);
+        }
+    }
     return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
 }
 

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "pdelta.h"
+
 namespace pdelta {
 
 int launch_pack_dispatch(int w_dtype, const void* W_f, const void* W_b, int64_t d_out,
@@ -20,6 +22,12 @@ constexpr int kSkinnyMaxM = 64;
 int launch_linear_skinny(int x_dtype, int y_dtype, int axis, const void* X, const void* W_b,
                          const uint32_t* B_packed, const uint16_t* v, void* Y, int64_t M,
                          int64_t d_out, int64_t d_in, hipStream_t stream);
+
+// Several decode-shaped layers in one launch.  Returns 1 when the batched kernel does not apply
+// (the caller then launches layer by layer), else 0 / -1.
+int launch_linear_skinny_batch(int x_dtype, int y_dtype, const ::pdelta_layer* layers_host,
+                               const ::pdelta_layer* layers_device, int n_layers, int64_t M,
+                               hipStream_t stream);
 
 // Prefill-shaped layer (many tokens): MFMA tile kernel.
 int launch_linear_gemm(int x_dtype, int y_dtype, int axis, const void* X, const void* W_b,

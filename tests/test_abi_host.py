@@ -21,7 +21,8 @@ def declared_functions():
 def test_library_exports_every_declared_function():
     names = declared_functions()
     assert {"pdelta_pack", "pdelta_linear_row", "pdelta_linear_col", "pdelta_patch",
-            "pdelta_pack_workspace_bytes", "pdelta_status_string"} <= set(names)
+            "pdelta_pack_workspace_bytes", "pdelta_status_string", "pdelta_linear_batch_plan",
+            "pdelta_linear_batch"} <= set(names)
     L = pd.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -68,6 +69,63 @@ def test_linear_argument_errors(fn):
     assert call_linear(fn, M=0) == pd.OK
     assert call_linear(fn, M=0, X=None, Y=None) == pd.OK
     assert call_linear(fn, M=0, d_in=33) == pd.ESHAPE                  # still validated
+
+
+def fake_layers(n=3, **edit):
+    arr = (pd.Layer * n)()
+    for k in range(n):
+        base = A + k * 0x10000000
+        arr[k] = pd.Layer(base, base + 0x1000000, base + 0x2000000, base + 0x3000000, base + 0x4000000,
+                          64 + 16 * k + 1, 128 * (k + 1), k % 2, -1)
+    for name, value in edit.items():
+        setattr(arr[1], name, value)
+    return arr
+
+
+def test_batch_plan_and_argument_errors():
+    L = pd.lib()
+    arr = fake_layers()
+    assert L.pdelta_linear_batch_plan(arr, 3) == pd.OK
+    # first_block = running sum of ceil(d_out / 16): 65 -> 5 blocks, 81 -> 6 blocks
+    assert [arr[k].first_block for k in range(3)] == [0, 5, 11]
+    assert L.pdelta_linear_batch_plan(None, 0) == pd.OK
+    assert L.pdelta_linear_batch_plan(None, 2) == pd.EINVAL
+    assert L.pdelta_linear_batch_plan(arr, -1) == pd.EINVAL
+    assert L.pdelta_linear_batch_plan(fake_layers(axis=2), 3) == pd.EINVAL
+    assert L.pdelta_linear_batch_plan(fake_layers(d_in=100), 3) == pd.ESHAPE
+    assert L.pdelta_linear_batch_plan(fake_layers(d_out=0), 3) == pd.EINVAL
+
+    dev = A + 0x70000000
+
+    def run(a, n=3, M=2, xdt=pd.F16, ydt=pd.F16, d=dev):
+        return L.pdelta_linear_batch(a, d, n, M, xdt, ydt, None)
+
+    assert run(arr, M=0) == pd.OK                                      # empty batch: host-side no-op
+    assert run(arr, n=0) == pd.OK
+    assert run(None, n=0, d=None) == pd.OK
+    assert run(arr, n=-1) == pd.EINVAL
+    assert run(arr, M=-1) == pd.EINVAL
+    assert run(None) == pd.EINVAL
+    assert run(arr, d=None) == pd.EINVAL
+    assert run(arr, d=dev + 8) == pd.EALIGN
+    assert run(arr, xdt=pd.F32) == pd.EDTYPE
+    assert run(arr, ydt=9) == pd.EDTYPE
+    assert run(fake_layers(), M=0) == pd.EINVAL                        # never planned
+    for name in ("X", "W_b", "B_packed", "v", "Y"):
+        bad = fake_layers(**{name: None})
+        assert L.pdelta_linear_batch_plan(bad, 3) == pd.OK             # the plan looks at shapes only
+        assert run(bad) == pd.EINVAL
+        bad = fake_layers(**{name: A + 0x60000008})
+        L.pdelta_linear_batch_plan(bad, 3)
+        assert run(bad) == pd.EALIGN
+    edited = fake_layers()
+    L.pdelta_linear_batch_plan(edited, 3)
+    edited[1].d_out = 300                                              # shape edited after planning
+    assert run(edited, M=0) == pd.EINVAL
+    alias = fake_layers()
+    alias[1].Y = alias[1].W_b
+    L.pdelta_linear_batch_plan(alias, 3)
+    assert run(alias) == pd.EINVAL
 
 
 def call_pack(Wf=A, Wb=A + 0x1000000, d_out=64, d_in=128, dt=pd.F16, B=A + 0x2000000,
