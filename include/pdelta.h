@@ -148,6 +148,12 @@ int pdelta_patch(const void* W_b, const uint32_t* B_packed, const uint16_t* v, i
  * When the layers do not fit the batched decode kernel (M > 16, d_in not a multiple of 128, or
  * operand slabs too large for LDS) the call launches them one by one in order, with the same
  * results.  M = 0 or n_layers = 0 is a no-op.
+ * Ownership and errors: layers_host is host memory, layers_device device memory holding the
+ * same n_layers descriptors (16-byte aligned, PDELTA_EALIGN); both stay the caller's and must
+ * stay valid until the stream has run the call.  Each layer is checked like a single-layer call
+ * (same error codes); a descriptor whose first_block does not match the plan gives
+ * PDELTA_EINVAL.  The Y of a layer must not overlap any buffer of another layer of the batch
+ * (all layers run concurrently); this is the caller's obligation and is not checked.
  */
 typedef struct pdelta_layer {
     const void* X;            /* [M, d_in] */
