@@ -265,7 +265,14 @@ def main() -> int:
         out["pack"] = {"workload": "config4: pdelta_pack over the 224 layers, fp16, 5% zero deltas, v_row + v_col",
                        "bytes": pack_bytes, "ms": round(ms, 3), "GB/s": round(pack_bytes / ms / 1e6, 1),
                        "frac_hbm": round(pack_bytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
-        del Wfs, outs
+        # the same 224 layers through the model-wide entry point: two launches instead of 448
+        pplan = pd.pdelta_pack_batch_plan([(Wf, l[3]) for l, Wf in zip(layers, Wfs)], out=outs)
+        timed(lambda: pd.pdelta_pack_batch(pplan), 1)
+        msb = timed(lambda: pd.pdelta_pack_batch(pplan), 5) / 5
+        out["pack"]["batched"] = {"entry_point": "pdelta_pack_batch", "ms": round(msb, 3),
+                                  "GB/s": round(pack_bytes / msb / 1e6, 1),
+                                  "frac_hbm": round(pack_bytes / msb / 1e6 / HBM_PEAK_GBS, 4)}
+        del Wfs, outs, pplan
         torch.cuda.empty_cache()
 
     # ---------------- patch: merge the delta into all 224 layers, out of place -----------------
@@ -282,6 +289,22 @@ def main() -> int:
         out["patch"] = {"workload": "pdelta_patch over the 224 layers (read W_b + signs, write W_hat), fp16",
                         "bytes": patch_bytes, "ms": round(ms, 3), "GB/s": round(patch_bytes / ms / 1e6, 1),
                         "frac_hbm": round(patch_bytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        # model-wide merge in place (one launch): the hot-swap of a fine-tune onto resident base
+        # weights; a second call with negated scales swaps it out again
+        ROW_COL = {"row": pd.ROW, "col": pd.COL}
+        swap_in = pd.pdelta_patch_batch_plan([(W_b, B, v, ROW_COL[axis], W_b) for (_, _, axis, W_b, B, v) in layers])
+        swap_out = pd.pdelta_patch_batch_plan([(W_b, B, -v, ROW_COL[axis], W_b) for (_, _, axis, W_b, B, v) in layers])
+
+        def swap_pass():
+            pd.pdelta_patch_batch(swap_in)
+            pd.pdelta_patch_batch(swap_out)
+
+        timed(swap_pass, 1)
+        msb = timed(swap_pass, 3) / 6
+        out["patch"]["batched_in_place"] = {"entry_point": "pdelta_patch_batch", "ms_per_model_swap": round(msb, 3),
+                                            "GB/s": round(patch_bytes / msb / 1e6, 1),
+                                            "frac_hbm": round(patch_bytes / msb / 1e6 / HBM_PEAK_GBS, 4)}
+        del swap_in, swap_out
     layers = None
     torch.cuda.empty_cache()
 

@@ -58,8 +58,10 @@ typedef enum {
     PDELTA_EHIP = -6        /* a kernel launch failed; hipGetLastError has been consumed */
 } pdelta_status;
 
-/* Bytes of device scratch pdelta_pack needs for these dimensions (partial sums of |dW| per
- * row and per column).  Returns 0 for non-positive dimensions. */
+/* Bytes of device scratch pdelta_pack needs for these dimensions: fp64 partial sums of |dW|,
+ * one per (row, tile of 1024 columns) and one per (tile of 64 rows, column), i.e.
+ * 8 * (ceil(d_in / 1024) * d_out + ceil(d_out / 64) * d_in).  Returns 0 for non-positive
+ * dimensions. */
 size_t pdelta_pack_workspace_bytes(int64_t d_out, int64_t d_in);
 
 /*
@@ -77,11 +79,12 @@ size_t pdelta_pack_workspace_bytes(int64_t d_out, int64_t d_in);
  *   v_col      out  FP16 [d_in],  may be NULL
  *   workspace  scratch, >= pdelta_pack_workspace_bytes(d_out, d_in) bytes, 16-byte aligned;
  *              contents on entry are ignored, contents on exit are unspecified
- * Exactness: for FP16 inputs the sums are accumulated as 64-bit integers in units of 2^-24,
- * so the result does not depend on the order of accumulation and is bit-reproducible; it
+ * Exactness: for FP16 inputs every difference is exact and the sums are formed without
+ * rounding (fp64 inside a tile, 64-bit integers in units of 2^-24 across tiles), so the result
  * equals the fp64 reference bit for bit while each sum of |dW| stays below 2^29.  For BF16
  * inputs sums are accumulated in fp64 (exact whenever all |dW| are multiples of a common
  * 2^-q and the sum stays below 2^(53-q); otherwise within one FP16 ulp of the exact mean).
+ * Partial sums are added in a fixed order: results are bit-reproducible for both dtypes.
  * d_out and d_in may each be at most 2^22.
  */
 int pdelta_pack(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, int w_dtype,
@@ -170,6 +173,48 @@ int pdelta_linear_batch_plan(pdelta_layer* layers_host, int32_t n_layers);
 
 int pdelta_linear_batch(const pdelta_layer* layers_host, const pdelta_layer* layers_device,
                         int32_t n_layers, int64_t M, int x_dtype, int y_dtype, void* stream);
+
+/*
+ * Merge the deltas of many layers in one launch: the paper's "Model-wide application from a
+ * saved delta file" (every module of the model is patched; Eq. 1 per layer).  Each layer computes
+ * exactly what pdelta_patch computes.  Descriptors are pdelta_layer records planned with
+ * pdelta_linear_batch_plan: W_b, B_packed, v, d_out, d_in and axis as there, Y is W_out (same
+ * dtype as W_b; may equal W_b for an in-place merge), X is ignored.  Host and device copies of
+ * the array are passed as in pdelta_linear_batch; ownership and error rules are the same.  The
+ * W_out of a layer must not overlap any buffer of another layer of the batch (not checked).
+ */
+int pdelta_patch_batch(const pdelta_layer* layers_host, const pdelta_layer* layers_device,
+                       int32_t n_layers, int w_dtype, void* stream);
+
+/*
+ * pdelta_pack for many layers in two launches (all tiles, then all scale vectors): the paper's
+ * compression of a whole model, module by module (per-layer compression algorithm applied to
+ * every linear layer).  Each job computes exactly what pdelta_pack computes, with its own
+ * workspace of at least pdelta_pack_workspace_bytes(d_out, d_in) bytes (workspaces of different
+ * jobs must not overlap; outputs of a job must not overlap anything of another job: not checked).
+ * pdelta_pack_batch_plan (host only) checks the shapes and fills first_tile, first_fin_block and
+ * tile_blocks; the caller copies the planned array to the device and passes both copies, as in
+ * pdelta_linear_batch.  n_jobs = 0 is a no-op.
+ */
+typedef struct pdelta_pack_job {
+    const void* W_f;          /* [d_out, d_in] */
+    const void* W_b;          /* [d_out, d_in] */
+    uint32_t* B_packed;       /* out [d_out, d_in/32] */
+    uint16_t* v_row;          /* out FP16 [d_out], may be NULL */
+    uint16_t* v_col;          /* out FP16 [d_in],  may be NULL */
+    void* workspace;          /* scratch of this job */
+    size_t workspace_bytes;
+    int64_t d_out, d_in;
+    int32_t first_tile;       /* the next three are filled by pdelta_pack_batch_plan */
+    int32_t first_fin_block;
+    int32_t tile_blocks;
+    int32_t reserved;
+} pdelta_pack_job;
+
+int pdelta_pack_batch_plan(pdelta_pack_job* jobs_host, int32_t n_jobs);
+
+int pdelta_pack_batch(const pdelta_pack_job* jobs_host, const pdelta_pack_job* jobs_device,
+                      int32_t n_jobs, int w_dtype, void* stream);
 
 /* Static, human-readable name of a pdelta_status value. */
 const char* pdelta_status_string(int status);

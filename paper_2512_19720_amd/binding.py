@@ -33,6 +33,15 @@ class Layer(ctypes.Structure):
                 ("d_in", ctypes.c_int64), ("axis", ctypes.c_int32), ("first_block", ctypes.c_int32)]
 
 
+class PackJob(ctypes.Structure):
+    """Mirror of the C struct ``pdelta_pack_job``."""
+    _fields_ = [("W_f", ctypes.c_void_p), ("W_b", ctypes.c_void_p), ("B_packed", ctypes.c_void_p),
+                ("v_row", ctypes.c_void_p), ("v_col", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_size_t), ("d_out", ctypes.c_int64), ("d_in", ctypes.c_int64),
+                ("first_tile", ctypes.c_int32), ("first_fin_block", ctypes.c_int32),
+                ("tile_blocks", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
 def lib() -> ctypes.CDLL:
     """The loaded C library.  Raises if it has not been built (no fallback exists)."""
     global _lib
@@ -57,6 +66,12 @@ def lib() -> ctypes.CDLL:
         L.pdelta_linear_batch_plan.argtypes = [ctypes.POINTER(Layer), ctypes.c_int32]
         L.pdelta_linear_batch.restype = i32
         L.pdelta_linear_batch.argtypes = [ctypes.POINTER(Layer), vp, ctypes.c_int32, i64, i32, i32, vp]
+        L.pdelta_patch_batch.restype = i32
+        L.pdelta_patch_batch.argtypes = [ctypes.POINTER(Layer), vp, ctypes.c_int32, i32, vp]
+        L.pdelta_pack_batch_plan.restype = i32
+        L.pdelta_pack_batch_plan.argtypes = [ctypes.POINTER(PackJob), ctypes.c_int32]
+        L.pdelta_pack_batch.restype = i32
+        L.pdelta_pack_batch.argtypes = [ctypes.POINTER(PackJob), vp, ctypes.c_int32, i32, vp]
         L.pdelta_status_string.restype = ctypes.c_char_p
         L.pdelta_status_string.argtypes = [i32]
         _lib = L
@@ -203,3 +218,95 @@ def pdelta_linear_batch(plan: BatchPlan):
                                    plan.y_dtype, _stream())
     _check(rc, "pdelta_linear_batch")
     return plan.Y
+
+
+def _to_device(host_array, device) -> torch.Tensor:
+    return torch.frombuffer(bytearray(bytes(host_array)), dtype=torch.uint8).to(device)
+
+
+class PatchPlan:
+    """Host and device copies of a planned ``pdelta_layer`` array for ``pdelta_patch_batch``."""
+
+    def __init__(self, host, device, tensors, w_dtype):
+        self.host, self.device, self.tensors, self.w_dtype = host, device, tensors, w_dtype
+        self.W_out = [t[3] for t in tensors]
+
+    def __len__(self):
+        return len(self.host)
+
+
+def pdelta_patch_batch_plan(layers) -> PatchPlan:
+    """``layers``: sequence of ``(W_b, B_packed, v, axis)`` or ``(W_b, B_packed, v, axis, W_out)``;
+    pass ``W_out = W_b`` to merge in place, omit it to allocate the outputs."""
+    layers = list(layers)
+    if not layers:
+        raise ValueError("no layers")
+    host = (Layer * len(layers))()
+    tensors = []
+    dt = layers[0][0].dtype
+    for k, item in enumerate(layers):
+        W_b, B_packed, v, axis = item[:4]
+        W_out = item[4] if len(item) > 4 else torch.empty_like(W_b)
+        if W_b.dtype != dt or W_out.dtype != dt or W_out.shape != W_b.shape:
+            raise ValueError("layers of one batch share the weight dtype; W_out matches W_b")
+        d_out, d_in = W_b.shape
+        host[k] = Layer(None, _dev(W_b, "W_b"), _dev(B_packed, "B_packed"), _dev(v, "v"),
+                        _dev(W_out, "W_out"), d_out, d_in, axis, 0)
+        tensors.append((W_b, B_packed, v, W_out))
+    _check(lib().pdelta_linear_batch_plan(host, len(layers)), "pdelta_linear_batch_plan")
+    return PatchPlan(host, _to_device(host, tensors[0][0].device), tensors, dtype_code(dt))
+
+
+def pdelta_patch_batch(plan: PatchPlan):
+    """Merge every layer of the plan in one launch; returns the list of W_out tensors."""
+    rc = lib().pdelta_patch_batch(plan.host, plan.device.data_ptr(), len(plan), plan.w_dtype, _stream())
+    _check(rc, "pdelta_patch_batch")
+    return plan.W_out
+
+
+class PackPlan:
+    """Host and device copies of a planned ``pdelta_pack_job`` array plus outputs and workspaces."""
+
+    def __init__(self, host, device, tensors, w_dtype):
+        self.host, self.device, self.tensors, self.w_dtype = host, device, tensors, w_dtype
+        self.out = [(t[2], t[3], t[4]) for t in tensors]
+
+    def __len__(self):
+        return len(self.host)
+
+
+def pdelta_pack_batch_plan(pairs, want_row: bool = True, want_col: bool = True, out=None) -> PackPlan:
+    """``pairs``: sequence of ``(W_f, W_b)``.  Outputs ``(B_packed, v_row, v_col)`` per pair are
+    allocated unless ``out`` gives them; every job gets its own workspace."""
+    pairs = list(pairs)
+    if not pairs:
+        raise ValueError("no layers")
+    host = (PackJob * len(pairs))()
+    tensors = []
+    dt = pairs[0][1].dtype
+    for k, (W_f, W_b) in enumerate(pairs):
+        if W_f.shape != W_b.shape or W_f.dtype != dt or W_b.dtype != dt:
+            raise ValueError("W_f and W_b must agree in shape; one dtype per batch")
+        d_out, d_in = W_b.shape
+        dev = W_b.device
+        if out is None:
+            B = torch.empty((d_out, d_in // 32), dtype=torch.int32, device=dev)
+            v_row = torch.empty(d_out, dtype=torch.float16, device=dev) if want_row else None
+            v_col = torch.empty(d_in, dtype=torch.float16, device=dev) if want_col else None
+        else:
+            B, v_row, v_col = out[k]
+        ws = torch.empty(pdelta_pack_workspace_bytes(d_out, d_in), dtype=torch.uint8, device=dev)
+        host[k] = PackJob(_dev(W_f, "W_f"), _dev(W_b, "W_b"), _dev(B, "B_packed"),
+                          _dev(v_row, "v_row") if v_row is not None else None,
+                          _dev(v_col, "v_col") if v_col is not None else None,
+                          _dev(ws, "workspace"), ws.numel(), d_out, d_in, 0, 0, 0, 0)
+        tensors.append((W_f, W_b, B, v_row, v_col, ws))
+    _check(lib().pdelta_pack_batch_plan(host, len(pairs)), "pdelta_pack_batch_plan")
+    return PackPlan(host, _to_device(host, tensors[0][0].device), tensors, dtype_code(dt))
+
+
+def pdelta_pack_batch(plan: PackPlan):
+    """Pack every pair of the plan (two launches); returns [(B_packed, v_row, v_col), ...]."""
+    rc = lib().pdelta_pack_batch(plan.host, plan.device.data_ptr(), len(plan), plan.w_dtype, _stream())
+    _check(rc, "pdelta_pack_batch")
+    return plan.out

@@ -98,12 +98,12 @@ extern "C" {
 size_t pdelta_pack_workspace_bytes(int64_t d_out, int64_t d_in)
 {
     if (d_out <= 0 || d_in <= 0) return 0;
-    return (size_t)(d_out + d_in) * 8;
+    return pdelta::pack_workspace_bytes(d_out, d_in);
 }
 
-int pdelta_pack(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, int w_dtype,
-                uint32_t* B_packed, uint16_t* v_row, uint16_t* v_col, void* workspace,
-                size_t workspace_bytes, void* stream)
+static int pack_check(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, int w_dtype,
+                      uint32_t* B_packed, uint16_t* v_row, uint16_t* v_col, void* workspace,
+                      size_t workspace_bytes)
 {
     using namespace pdelta;
     if (W_f == nullptr || W_b == nullptr || B_packed == nullptr) return PDELTA_EINVAL;
@@ -118,8 +118,63 @@ int pdelta_pack(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, i
     const size_t w_bytes = (size_t)d_out * d_in * 2, b_bytes = (size_t)d_out * d_in / 8;
     if (overlaps(B_packed, b_bytes, W_f, w_bytes) || overlaps(B_packed, b_bytes, W_b, w_bytes))
         return PDELTA_EINVAL;
+    return PDELTA_OK;
+}
+
+int pdelta_pack(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, int w_dtype,
+                uint32_t* B_packed, uint16_t* v_row, uint16_t* v_col, void* workspace,
+                size_t workspace_bytes, void* stream)
+{
+    using namespace pdelta;
+    if (const int rc = pack_check(W_f, W_b, d_out, d_in, w_dtype, B_packed, v_row, v_col, workspace,
+                                  workspace_bytes))
+        return rc;
     const int rc = launch_pack_dispatch(w_dtype, W_f, W_b, d_out, d_in, B_packed, v_row, v_col,
                                         workspace, (hipStream_t)stream);
+    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+}
+
+int pdelta_pack_batch_plan(pdelta_pack_job* jobs_host, int32_t n_jobs)
+{
+    using namespace pdelta;
+    if (n_jobs < 0 || (n_jobs > 0 && jobs_host == nullptr)) return PDELTA_EINVAL;
+    int64_t tile = 0, fin = 0;
+    for (int32_t j = 0; j < n_jobs; ++j) {
+        pdelta_pack_job& J = jobs_host[j];
+        if (const int rc = check_dims(J.d_out, J.d_in)) return rc;
+        if (tile > 0x7FFFFFFF || fin > 0x7FFFFFFF) return PDELTA_ESHAPE;
+        J.first_tile = (int32_t)tile;
+        J.first_fin_block = (int32_t)fin;
+        J.tile_blocks = pack_batch_tile_blocks(J.d_out);
+        J.reserved = 0;
+        tile += pack_batch_tiles(J.d_out, J.d_in, J.tile_blocks);
+        fin += pack_batch_fin_blocks(J.d_out, J.d_in);
+    }
+    if (tile > 0x7FFFFFFF || fin > 0x7FFFFFFF) return PDELTA_ESHAPE;
+    return PDELTA_OK;
+}
+
+int pdelta_pack_batch(const pdelta_pack_job* jobs_host, const pdelta_pack_job* jobs_device,
+                      int32_t n_jobs, int w_dtype, void* stream)
+{
+    using namespace pdelta;
+    if (n_jobs < 0) return PDELTA_EINVAL;
+    if (n_jobs == 0) return PDELTA_OK;
+    if (jobs_host == nullptr || jobs_device == nullptr) return PDELTA_EINVAL;
+    if (misaligned(jobs_device)) return PDELTA_EALIGN;
+    int64_t tile = 0, fin = 0;
+    for (int32_t j = 0; j < n_jobs; ++j) {
+        const pdelta_pack_job& J = jobs_host[j];
+        if (const int rc = pack_check(J.W_f, J.W_b, J.d_out, J.d_in, w_dtype, J.B_packed, J.v_row, J.v_col,
+                                      J.workspace, J.workspace_bytes))
+            return rc;
+        if (J.first_tile != (int32_t)tile || J.first_fin_block != (int32_t)fin ||
+            J.tile_blocks != pack_batch_tile_blocks(J.d_out))
+            return PDELTA_EINVAL;                                       // not planned, or edited
+        tile += pack_batch_tiles(J.d_out, J.d_in, J.tile_blocks);
+        fin += pack_batch_fin_blocks(J.d_out, J.d_in);
+    }
+    const int rc = launch_pack_batch(w_dtype, jobs_host, jobs_device, n_jobs, (hipStream_t)stream);
     return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
 }
 
@@ -139,8 +194,8 @@ int pdelta_linear_col(const void* X, const void* W_b, const uint32_t* B_packed,
                                  PDELTA_COL, stream);
 }
 
-int pdelta_patch(const void* W_b, const uint32_t* B_packed, const uint16_t* v, int axis,
-                 void* W_out, int64_t d_out, int64_t d_in, int w_dtype, void* stream)
+static int patch_check(const void* W_b, const uint32_t* B_packed, const uint16_t* v, int axis,
+                       void* W_out, int64_t d_out, int64_t d_in, int w_dtype)
 {
     using namespace pdelta;
     if (W_b == nullptr || B_packed == nullptr || v == nullptr || W_out == nullptr) return PDELTA_EINVAL;
@@ -154,8 +209,36 @@ int pdelta_patch(const void* W_b, const uint32_t* B_packed, const uint16_t* v, i
     if (overlaps(W_out, w_bytes, B_packed, w_bytes / 16) ||
         overlaps(W_out, w_bytes, v, (size_t)(axis == PDELTA_ROW ? d_out : d_in) * 2))
         return PDELTA_EINVAL;
+    return PDELTA_OK;
+}
+
+int pdelta_patch(const void* W_b, const uint32_t* B_packed, const uint16_t* v, int axis,
+                 void* W_out, int64_t d_out, int64_t d_in, int w_dtype, void* stream)
+{
+    using namespace pdelta;
+    if (const int rc = patch_check(W_b, B_packed, v, axis, W_out, d_out, d_in, w_dtype)) return rc;
     const int rc = launch_patch_dispatch(w_dtype, axis, W_b, B_packed, v, W_out, d_out, d_in,
                                          (hipStream_t)stream);
+    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+}
+
+int pdelta_patch_batch(const pdelta_layer* layers_host, const pdelta_layer* layers_device,
+                       int32_t n_layers, int w_dtype, void* stream)
+{
+    using namespace pdelta;
+    if (n_layers < 0) return PDELTA_EINVAL;
+    if (n_layers == 0) return PDELTA_OK;
+    if (layers_host == nullptr || layers_device == nullptr) return PDELTA_EINVAL;
+    if (misaligned(layers_device)) return PDELTA_EALIGN;
+    int64_t first = 0;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const pdelta_layer& L = layers_host[l];
+        if (const int rc = patch_check(L.W_b, L.B_packed, L.v, L.axis, L.Y, L.d_out, L.d_in, w_dtype))
+            return rc;
+        if (L.first_block != (int32_t)first) return PDELTA_EINVAL;     // not planned, or edited
+        first += (L.d_out + 15) / 16;
+    }
+    const int rc = launch_patch_batch(w_dtype, layers_host, layers_device, n_layers, (hipStream_t)stream);
     return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
 }
 

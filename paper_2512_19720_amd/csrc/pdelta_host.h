@@ -9,9 +9,22 @@
 
 namespace pdelta {
 
+// Bytes of fp64 partial sums pdelta_pack writes for these dimensions.
+size_t pack_workspace_bytes(int64_t d_out, int64_t d_in);
+
 int launch_pack_dispatch(int w_dtype, const void* W_f, const void* W_b, int64_t d_out,
                          int64_t d_in, uint32_t* B_packed, uint16_t* v_row, uint16_t* v_col,
                          void* workspace, hipStream_t stream);
+
+// Batched pack: geometry helpers shared by the plan (host) and the launcher.
+int pack_batch_tile_blocks(int64_t d_out);
+int64_t pack_batch_tiles(int64_t d_out, int64_t d_in, int tile_blocks);
+int64_t pack_batch_fin_blocks(int64_t d_out, int64_t d_in);
+int launch_pack_batch(int w_dtype, const ::pdelta_pack_job* jobs_host, const ::pdelta_pack_job* jobs_device,
+                      int n_jobs, hipStream_t stream);
+
+int launch_patch_batch(int w_dtype, const ::pdelta_layer* layers_host, const ::pdelta_layer* layers_device,
+                       int n_layers, hipStream_t stream);
 
 int launch_patch_dispatch(int w_dtype, int axis, const void* W_b, const uint32_t* B_packed,
                           const uint16_t* v, void* W_out, int64_t d_out, int64_t d_in,

@@ -22,7 +22,8 @@ def test_library_exports_every_declared_function():
     names = declared_functions()
     assert {"pdelta_pack", "pdelta_linear_row", "pdelta_linear_col", "pdelta_patch",
             "pdelta_pack_workspace_bytes", "pdelta_status_string", "pdelta_linear_batch_plan",
-            "pdelta_linear_batch"} <= set(names)
+            "pdelta_linear_batch", "pdelta_patch_batch", "pdelta_pack_batch_plan",
+            "pdelta_pack_batch"} <= set(names)
     L = pd.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -37,7 +38,8 @@ def test_status_strings():
 
 
 def test_workspace_bytes():
-    assert pd.pdelta_pack_workspace_bytes(4096, 11008) == 8 * (4096 + 11008)
+    assert pd.pdelta_pack_workspace_bytes(4096, 11008) == 8 * (11 * 4096 + 64 * 11008)
+    assert pd.pdelta_pack_workspace_bytes(65, 32) == 8 * (1 * 65 + 2 * 32)
     assert pd.pdelta_pack_workspace_bytes(0, 32) == 0
     assert pd.pdelta_pack_workspace_bytes(32, -1) == 0
 
@@ -126,6 +128,99 @@ def test_batch_plan_and_argument_errors():
     alias[1].Y = alias[1].W_b
     L.pdelta_linear_batch_plan(alias, 3)
     assert run(alias) == pd.EINVAL
+
+
+def test_patch_batch_argument_errors():
+    L = pd.lib()
+    dev = A + 0x70000000
+
+    def run(a, n=3, dt=pd.F16, d=dev):
+        return L.pdelta_patch_batch(a, d, n, dt, None)
+
+    arr = fake_layers()
+    assert run(arr) == pd.EINVAL                                       # never planned
+    L.pdelta_linear_batch_plan(arr, 3)
+    assert run(arr, n=0) == pd.OK
+    assert run(arr, n=-1) == pd.EINVAL
+    assert run(None) == pd.EINVAL
+    assert run(arr, d=None) == pd.EINVAL
+    assert run(arr, d=dev + 4) == pd.EALIGN
+    assert run(arr, dt=pd.F32) == pd.EDTYPE
+    for name in ("W_b", "B_packed", "v", "Y"):
+        bad = fake_layers(**{name: None})
+        L.pdelta_linear_batch_plan(bad, 3)
+        assert run(bad) == pd.EINVAL
+        bad = fake_layers(**{name: A + 0x60000008})
+        L.pdelta_linear_batch_plan(bad, 3)
+        assert run(bad) == pd.EALIGN
+    ok = fake_layers(X=None)                                           # X is not used by the merge
+    L.pdelta_linear_batch_plan(ok, 3)
+    inplace = fake_layers()
+    inplace[1].Y = inplace[1].W_b                                      # in place is allowed
+    L.pdelta_linear_batch_plan(inplace, 3)
+    overlap = fake_layers()
+    overlap[1].Y = overlap[1].W_b + 64                                 # partial overlap is not
+    L.pdelta_linear_batch_plan(overlap, 3)
+    assert run(overlap) == pd.EINVAL
+    # valid descriptors would launch: not exercised without a GPU
+    del ok, inplace
+
+
+def fake_jobs(n=3, **edit):
+    arr = (pd.PackJob * n)()
+    for k in range(n):
+        base = A + k * 0x10000000
+        d_out, d_in = 100 + 500 * k, 1024 * (k + 1) + 32
+        arr[k] = pd.PackJob(base, base + 0x1000000, base + 0x2000000, base + 0x3000000, base + 0x3100000,
+                            base + 0x4000000, pd.pdelta_pack_workspace_bytes(d_out, d_in), d_out, d_in, -1, -1, -1, 0)
+    for name, value in edit.items():
+        setattr(arr[1], name, value)
+    return arr
+
+
+def test_pack_batch_plan_and_argument_errors():
+    L = pd.lib()
+    arr = fake_jobs()
+    assert L.pdelta_pack_batch_plan(arr, 3) == pd.OK
+    # job 0: 100 x 1056 -> 64-row tiles (2 blocks): 2 row tiles x 2 column tiles; 2 + 17 finalize blocks
+    # job 1: 600 x 2080 -> 128-row tiles (4 blocks): 5 x 3 tiles; 10 + 33 finalize blocks
+    assert [arr[k].tile_blocks for k in range(3)] == [2, 4, 4]
+    assert [arr[k].first_tile for k in range(3)] == [0, 4, 19]
+    assert [arr[k].first_fin_block for k in range(3)] == [0, 19, 62]
+    assert L.pdelta_pack_batch_plan(None, 0) == pd.OK
+    assert L.pdelta_pack_batch_plan(None, 1) == pd.EINVAL
+    assert L.pdelta_pack_batch_plan(fake_jobs(d_in=100), 3) == pd.ESHAPE
+    assert L.pdelta_pack_batch_plan(fake_jobs(d_out=-4), 3) == pd.EINVAL
+    dev = A + 0x70000000
+
+    def run(a, n=3, dt=pd.F16, d=dev):
+        return L.pdelta_pack_batch(a, d, n, dt, None)
+
+    assert run(arr, n=0) == pd.OK
+    assert run(arr, n=-2) == pd.EINVAL
+    assert run(None) == pd.EINVAL
+    assert run(arr, d=None) == pd.EINVAL
+    assert run(arr, d=dev + 8) == pd.EALIGN
+    assert run(arr, dt=pd.F32) == pd.EDTYPE
+    assert run(fake_jobs()) == pd.EINVAL                               # never planned
+    for name in ("W_f", "W_b", "B_packed"):
+        bad = fake_jobs(**{name: None})
+        L.pdelta_pack_batch_plan(bad, 3)
+        assert run(bad) == pd.EINVAL
+    bad = fake_jobs(workspace=None)
+    L.pdelta_pack_batch_plan(bad, 3)
+    assert run(bad) == pd.EWORKSPACE
+    bad = fake_jobs(workspace_bytes=64)
+    L.pdelta_pack_batch_plan(bad, 3)
+    assert run(bad) == pd.EWORKSPACE
+    bad = fake_jobs(v_col=A + 0x60000002)
+    L.pdelta_pack_batch_plan(bad, 3)
+    assert run(bad) == pd.EALIGN
+    edited = fake_jobs()
+    L.pdelta_pack_batch_plan(edited, 3)
+    edited[0].d_out = 4096                                             # shape edited after planning
+    edited[0].workspace_bytes = 1 << 30
+    assert run(edited) == pd.EINVAL
 
 
 def call_pack(Wf=A, Wb=A + 0x1000000, d_out=64, d_in=128, dt=pd.F16, B=A + 0x2000000,
