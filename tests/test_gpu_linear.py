@@ -65,7 +65,10 @@ def test_decode_stack_shapes_batch1(shape, dtype):
 @pytest.mark.parametrize("M,d_out,d_in", [(65, 128, 64), (200, 100, 96), (256, 300, 160), (129, 257, 1024),
                                           (128, 128, 32), (1000, 384, 512)])
 @pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
-def test_prefill_path_small_and_ragged(M, d_out, d_in, dtype):
+@pytest.mark.parametrize("kernel", ["two_per_cu", "pipelined"])
+def test_prefill_path_small_and_ragged(M, d_out, d_in, dtype, kernel, monkeypatch):
+    # both prefill kernels on every shape (the library would pick by tile count)
+    monkeypatch.setenv("PDELTA_TUNE", "gemm_pipe=1" if kernel == "pipelined" else "gemm_pipe=0")
     L = make_case(d_out, d_in, M, dtype, "row", synth.seed_for(2, M + d_out + d_in))
     run_both_axes(L, (pd.F32, pd.F16 if dtype == synth.F16 else pd.BF16), f"prefill {M}x{d_out}x{d_in} dt={dtype}")
 
@@ -91,9 +94,13 @@ def test_empty_batch_is_a_no_op():
 
 
 @pytest.mark.parametrize("shape", synth.PREFILL_SHAPES)
-def test_config2_prefill_full_size_sampled_outputs(shape):
-    """bf16, M = 2048, the benchmark's launch configuration; 600 sampled outputs, each an fp64 dot
-    product by the oracle, plus whole rows and columns of the output tile grid's corners."""
+@pytest.mark.parametrize("kernel", ["default", "pipelined"])
+def test_config2_prefill_full_size_sampled_outputs(shape, kernel, monkeypatch):
+    """bf16, M = 2048, the benchmark's launch configuration (the library's own choice of kernel,
+    and the pipelined kernel forced); 600 sampled outputs, each an fp64 dot product by the
+    oracle, plus whole rows and columns of the output tile grid's corners."""
+    if kernel == "pipelined":
+        monkeypatch.setenv("PDELTA_TUNE", "gemm_pipe=1")
     d_out, d_in = shape
     M = 2048
     seed = synth.seed_for(2, d_out % 1000 + d_in % 1000)
