@@ -10,7 +10,7 @@ each with its own events, the other workloads of the path (prefill GEMM shapes, 
 decode stack, the offline pack of that stack, the in-place patch) and the CPU oracle on a
 bounded sample; they are reported as extra objects on the same JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--skip prefill,stack,pack,patch,cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--skip variants,prefill,stack,pack,patch,cpu]
 """
 from __future__ import annotations
 
@@ -157,6 +157,43 @@ def main() -> int:
                    "bytes_per_step": step_bytes},
         "roofline": roofline, "decode_cases": per_case, "wall_s_timed_region": round(wall_s, 4),
     }
+    # ---------------- multi-variant decode: R requests share W_b, each has its own delta -------
+    if "variants" not in skip:
+        R, nsets = 16, 12                       # 12 x (32 MiB W_b + 16 x 2 MiB signs) = 768 MiB
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(synth.seed_for(1, 950))
+        XR = synth.x_device(R, K, synth.F16, synth.seed_for(1, 951), dev)
+        YR = torch.empty((R, N), dtype=f16, device=dev)
+        vsets = []
+        for si in range(nsets):
+            signs = [torch.randint(-2 ** 31, 2 ** 31 - 1, (N, K // 32), dtype=torch.int32, device=dev, generator=gen)
+                     for _ in range(R)]
+            vsets.append((sets[si][0], pd.VariantSet([(signs[r], sets[(si + r) % len(sets)][2]) for r in range(R)], pd.ROW)))
+        vrot = [0]
+
+        def variants_call():
+            W_b, vs = vsets[vrot[0] % nsets]
+            vrot[0] += 1
+            pd.pdelta_linear_variants(XR, W_b, vs, out=YR)
+
+        def separate_calls():
+            W_b, vs = vsets[vrot[0] % nsets]
+            vrot[0] += 1
+            for r in range(R):
+                pd.pdelta_linear_row(XR[r:r + 1], W_b, vs.tensors[r][0], vs.tensors[r][1], out=YR[r:r + 1])
+
+        vbytes = 2 * N * K + R * (N * K // 8 + 2 * N + 2 * K + 2 * N)
+        timed(variants_call, 20)
+        msv = timed(variants_call, 120) / 120
+        timed(separate_calls, 2)
+        mss = timed(separate_calls, 12) / 12
+        out["variants"] = {"workload": f"{R} requests x 1 token, one 4096x4096 fp16 base, {R} sign/scale sets, row mode; "
+                                       f"{nsets} rotating buffer sets",
+                           "entry_point": "pdelta_linear_variants", "bytes_per_call": vbytes,
+                           "us": round(msv * 1e3, 2), "GB/s": round(vbytes / msv / 1e6, 1),
+                           "frac_hbm": round(vbytes / msv / 1e6 / HBM_PEAK_GBS, 4),
+                           "same_work_as_16_single_calls_us": round(mss * 1e3, 2)}
+        del vsets, XR, YR
     del sets
     torch.cuda.empty_cache()
 

@@ -216,6 +216,34 @@ int pdelta_pack_batch_plan(pdelta_pack_job* jobs_host, int32_t n_jobs);
 int pdelta_pack_batch(const pdelta_pack_job* jobs_host, const pdelta_pack_job* jobs_device,
                       int32_t n_jobs, int w_dtype, void* stream);
 
+/*
+ * Multi-variant decode: R requests of one token each share the base weights and each has its
+ * own 1-bit delta - many fine-tuned variants of one base served together (the setting of the
+ * paper's introduction).  Request r computes exactly what pdelta_linear_row / pdelta_linear_col
+ * computes for M = 1 with (B_r, v_r) (Eq. 1 inside the layer forward):
+ *   row:  Y[r,o] = sum_i X[r,i] W_b[o,i] + v_r[o] * sum_i X[r,i] B_r[o,i]
+ *   col:  Y[r,o] = sum_i X[r,i] W_b[o,i] +          sum_i (X[r,i] v_r[i]) B_r[o,i]
+ * but W_b is read once for all requests (2 + R/8 bytes per weight) when R <= 16 and d_in is a
+ * multiple of 128; otherwise the requests run one after the other with the same results.
+ * Arguments
+ *   X         in   [R, d_in], dtype x_dtype; row r is the token of request r
+ *   W_b       in   [d_out, d_in], same dtype
+ *   variants  in   R records {B_packed [d_out, d_in/32], v FP16 [d_out] (row) or [d_in] (col)};
+ *                  a HOST copy (validated here) and a DEVICE copy (read by the kernel) of the same
+ *                  array, both owned by the caller and valid until the stream has run the call
+ *   axis      PDELTA_ROW or PDELTA_COL, one mode for all requests of a call
+ *   Y         out  [R, d_out], dtype y_dtype; must not overlap any input
+ * R = 0 is a no-op.  Errors as for pdelta_linear_row, per variant.
+ */
+typedef struct pdelta_variant {
+    const uint32_t* B_packed;
+    const uint16_t* v;
+} pdelta_variant;
+
+int pdelta_linear_variants(const void* X, const void* W_b, const pdelta_variant* variants_host,
+                           const pdelta_variant* variants_device, int32_t R, int axis, void* Y,
+                           int64_t d_out, int64_t d_in, int x_dtype, int y_dtype, void* stream);
+
 /* Static, human-readable name of a pdelta_status value. */
 const char* pdelta_status_string(int status);
 

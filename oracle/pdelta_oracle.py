@@ -192,5 +192,14 @@ def linear_at(X, W_b, B_packed, v, axis: int, m_idx, o_idx, x_dtype: int = F16) 
     return out
 
 
+def linear_variants(X, W_b, Bs, vs, axis: int, x_dtype: int = F16) -> np.ndarray:
+    """R requests that share W_b: row r of the result is the delta linear layer (Eq. 1 inside
+    the layer forward) of token X[r] with request r's own (Bs[r], vs[r]).  Written out as what it
+    is: R independent single-token layers, one call of `linear` each."""
+    X = _bits16(X)
+    rows = [linear(X[r:r + 1], W_b, Bs[r], vs[r], axis, x_dtype)[0] for r in range(X.shape[0])]
+    return np.stack(rows) if rows else np.zeros((0, _bits16(W_b).shape[0]))
+
+
 def threads() -> int:
     return int(_load().pdelta_ref_threads())

@@ -33,6 +33,11 @@ class Layer(ctypes.Structure):
                 ("d_in", ctypes.c_int64), ("axis", ctypes.c_int32), ("first_block", ctypes.c_int32)]
 
 
+class Variant(ctypes.Structure):
+    """Mirror of the C struct ``pdelta_variant``."""
+    _fields_ = [("B_packed", ctypes.c_void_p), ("v", ctypes.c_void_p)]
+
+
 class PackJob(ctypes.Structure):
     """Mirror of the C struct ``pdelta_pack_job``."""
     _fields_ = [("W_f", ctypes.c_void_p), ("W_b", ctypes.c_void_p), ("B_packed", ctypes.c_void_p),
@@ -72,6 +77,9 @@ def lib() -> ctypes.CDLL:
         L.pdelta_pack_batch_plan.argtypes = [ctypes.POINTER(PackJob), ctypes.c_int32]
         L.pdelta_pack_batch.restype = i32
         L.pdelta_pack_batch.argtypes = [ctypes.POINTER(PackJob), vp, ctypes.c_int32, i32, vp]
+        L.pdelta_linear_variants.restype = i32
+        L.pdelta_linear_variants.argtypes = [vp, vp, ctypes.POINTER(Variant), vp, ctypes.c_int32, i32, vp, i64, i64,
+                                             i32, i32, vp]
         L.pdelta_status_string.restype = ctypes.c_char_p
         L.pdelta_status_string.argtypes = [i32]
         _lib = L
@@ -310,3 +318,35 @@ def pdelta_pack_batch(plan: PackPlan):
     rc = lib().pdelta_pack_batch(plan.host, plan.device.data_ptr(), len(plan), plan.w_dtype, _stream())
     _check(rc, "pdelta_pack_batch")
     return plan.out
+
+
+class VariantSet:
+    """Host and device copies of a ``pdelta_variant`` array plus the tensors they point to."""
+
+    def __init__(self, variants, axis: int):
+        variants = list(variants)
+        self.axis = axis
+        self.tensors = variants
+        self.host = (Variant * max(len(variants), 1))()
+        for r, (B_packed, v) in enumerate(variants):
+            self.host[r] = Variant(_dev(B_packed, "B_packed"), _dev(v, "v"))
+        self.device = _to_device(self.host, variants[0][0].device) if variants else None
+
+    def __len__(self):
+        return len(self.tensors)
+
+
+def pdelta_linear_variants(X, W_b, variants: VariantSet, out=None, out_dtype=None):
+    """Y[r] = X[r] W_b^T + delta of request r; ``variants`` holds R pairs (B_packed, v)."""
+    R, d_in = X.shape
+    d_out = W_b.shape[0]
+    if R != len(variants) or W_b.shape[1] != d_in or X.dtype != W_b.dtype:
+        raise ValueError("one token per variant; X and W_b must agree in d_in and dtype")
+    if out is None:
+        out = torch.empty((R, d_out), dtype=out_dtype or X.dtype, device=X.device)
+    rc = lib().pdelta_linear_variants(_dev(X, "X") or None, _dev(W_b, "W_b"), variants.host,
+                                      variants.device.data_ptr() if variants.device is not None else None,
+                                      R, variants.axis, _dev(out, "Y") or None, d_out, d_in,
+                                      dtype_code(X.dtype), dtype_code(out.dtype), _stream())
+    _check(rc, "pdelta_linear_variants")
+    return out

@@ -42,6 +42,12 @@ int launch_linear_skinny_batch(int x_dtype, int y_dtype, const ::pdelta_layer* l
                                const ::pdelta_layer* layers_device, int n_layers, int64_t M,
                                hipStream_t stream);
 
+// R requests (one token each) that share W_b and each have their own delta.  Returns 1 when the
+// fused kernel does not apply (R > 16 or d_in % 128 != 0), else 0 / -1.
+int launch_linear_variants(int x_dtype, int y_dtype, int axis, const void* X, const void* W_b,
+                           const ::pdelta_variant* variants_device, int R, void* Y, int64_t d_out,
+                           int64_t d_in, hipStream_t stream);
+
 // Prefill-shaped layer (many tokens): MFMA tile kernel.
 int launch_linear_gemm(int x_dtype, int y_dtype, int axis, const void* X, const void* W_b,
                        const uint32_t* B_packed, const uint16_t* v, void* Y, int64_t M,

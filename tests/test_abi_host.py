@@ -23,7 +23,7 @@ def test_library_exports_every_declared_function():
     assert {"pdelta_pack", "pdelta_linear_row", "pdelta_linear_col", "pdelta_patch",
             "pdelta_pack_workspace_bytes", "pdelta_status_string", "pdelta_linear_batch_plan",
             "pdelta_linear_batch", "pdelta_patch_batch", "pdelta_pack_batch_plan",
-            "pdelta_pack_batch"} <= set(names)
+            "pdelta_pack_batch", "pdelta_linear_variants"} <= set(names)
     L = pd.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -221,6 +221,40 @@ def test_pack_batch_plan_and_argument_errors():
     edited[0].d_out = 4096                                             # shape edited after planning
     edited[0].workspace_bytes = 1 << 30
     assert run(edited) == pd.EINVAL
+
+
+def test_linear_variants_argument_errors():
+    L = pd.lib()
+
+    def variants(n=3, **edit):
+        arr = (pd.Variant * n)()
+        for r in range(n):
+            arr[r] = pd.Variant(A + 0x2000000 + r * 0x100000, A + 0x3000000 + r * 0x10000)
+        for name, value in edit.items():
+            setattr(arr[1], name, value)
+        return arr
+
+    def run(arr, X=A, W=A + 0x1000000, dev=A + 0x5000000, R=3, axis=pd.ROW, Y=A + 0x4000000, d_out=64,
+            d_in=128, xdt=pd.F16, ydt=pd.F16):
+        return L.pdelta_linear_variants(X, W, arr, dev, R, axis, Y, d_out, d_in, xdt, ydt, None)
+
+    ok = variants()
+    assert run(ok, R=0) == pd.OK
+    assert run(None, R=0, dev=None, X=None, Y=None) == pd.OK
+    assert run(ok, R=0, d_in=100) == pd.ESHAPE                        # still validated
+    assert run(ok, R=-1) == pd.EINVAL
+    assert run(None) == pd.EINVAL
+    assert run(ok, dev=None) == pd.EINVAL
+    assert run(ok, dev=A + 0x5000008) == pd.EALIGN
+    assert run(ok, axis=5) == pd.EINVAL
+    assert run(ok, X=None) == pd.EINVAL
+    assert run(ok, Y=None) == pd.EINVAL
+    assert run(ok, d_in=48) == pd.ESHAPE
+    assert run(ok, xdt=pd.F32) == pd.EDTYPE
+    assert run(variants(B_packed=None)) == pd.EINVAL
+    assert run(variants(v=None)) == pd.EINVAL
+    assert run(variants(v=A + 0x3000002)) == pd.EALIGN
+    assert run(variants(B_packed=A + 0x4000000)) == pd.EINVAL         # Y overlaps a variant's signs
 
 
 def call_pack(Wf=A, Wb=A + 0x1000000, d_out=64, d_in=128, dt=pd.F16, B=A + 0x2000000,

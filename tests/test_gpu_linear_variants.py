@@ -1,0 +1,100 @@
+"""GPU parity of pdelta_linear_variants (R requests sharing W_b, each with its own delta) against
+the CPU oracle, under the tolerance rule of parity_util.py, and against R single-token calls of
+pdelta_linear_row / pdelta_linear_col."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pdelta_oracle as orc
+from paper_2512_19720_amd import binding as pd
+from paper_2512_19720_amd import synth
+from parity_util import DEV, check_y, f16_dev, gpu_linear, to_dev, words_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def make_variants(d_out, d_in, R, dtype, axis, seed):
+    """Shared base + R independent deltas: host bits, oracle packs, device tensors."""
+    base = synth.layer_host(d_out, d_in, max(R, 1), dtype, "row" if axis == orc.ROW else "col", seed)
+    Bs, vs = [], []
+    for r in range(R):
+        Lr = synth.layer_host(d_out, d_in, 1, dtype, "row" if axis == orc.ROW else "col", seed + 1000 + r)
+        B, v_row, v_col = orc.pack(Lr["dW"], np.zeros_like(Lr["dW"]), dtype)
+        Bs.append(B)
+        vs.append(v_row if axis == orc.ROW else v_col)
+    X = base["X"][:R]
+    dev = {"X": to_dev(X, dtype), "W_b": to_dev(base["W_b"], dtype),
+           "variants": [(words_dev(B), f16_dev(v)) for B, v in zip(Bs, vs)]}
+    return X, base["W_b"], Bs, vs, dev
+
+
+@pytest.mark.parametrize("R", [1, 3, 8, 9, 16])
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("axis", [orc.ROW, orc.COL])
+def test_fused_kernel_matches_oracle(R, dtype, axis):
+    for d_out, d_in in ((64, 256), (100, 1152), (7, 128)):
+        X, W_b, Bs, vs, d = make_variants(d_out, d_in, R, dtype, axis, synth.seed_for(1, 3000 + 17 * R + d_out))
+        ref = orc.linear_variants(X, W_b, Bs, vs, axis, dtype)
+        vset = pd.VariantSet(d["variants"], axis)
+        for yd in (torch.float32, torch.float16 if dtype == synth.F16 else torch.bfloat16):
+            Y = torch.full((R, d_out), float("nan"), dtype=yd, device=DEV)     # every entry must be written
+            pd.pdelta_linear_variants(d["X"], d["W_b"], vset, out=Y)
+            torch.cuda.synchronize()
+            check_y(Y, ref, f"variants R={R} {d_out}x{d_in} dt={dtype} axis={axis} y={yd}")
+
+
+@pytest.mark.parametrize("axis", [orc.ROW, orc.COL])
+def test_decode_layer_4096_sixteen_variants(axis):
+    R = 16
+    X, W_b, Bs, vs, d = make_variants(4096, 4096, R, synth.F16, axis, synth.seed_for(1, 4000 + axis))
+    ref = orc.linear_variants(X, W_b, Bs, vs, axis, synth.F16)
+    vset = pd.VariantSet(d["variants"], axis)
+    Y = pd.pdelta_linear_variants(d["X"], d["W_b"], vset, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check_y(Y, ref, f"4096x4096 R=16 axis={axis}")
+    # against sixteen single-token calls of the ordinary entry points (different summation order:
+    # close, not bit-equal)
+    for r in (0, 7, 8, 15):
+        B_r, v_r = d["variants"][r]
+        single = gpu_linear(axis, d["X"][r:r + 1].contiguous(), d["W_b"], B_r, v_r, torch.float32)
+        assert torch.allclose(single[0], Y[r], rtol=2e-3, atol=2e-3 * float(Y[r].abs().mean()))
+
+
+@pytest.mark.parametrize("R,d_in,stage", [(7, 11008, 1), (20, 384, 0), (33, 256, 1), (5, 128, 0)])
+def test_chunked_launches_and_sign_words_in_registers(R, d_in, stage, monkeypatch):
+    # d_in = 11008: only six sign slabs fit in LDS, so 7 requests take two passes; stage = 0
+    # forces the variant that keeps the sign words in registers (8 requests per pass)
+    monkeypatch.setenv("PDELTA_TUNE", f"var_stage={stage}")
+    d_out = 40
+    for axis in (orc.ROW, orc.COL):
+        X, W_b, Bs, vs, d = make_variants(d_out, d_in, R, synth.F16, axis, synth.seed_for(1, 6000 + R))
+        ref = orc.linear_variants(X, W_b, Bs, vs, axis, synth.F16)
+        Y = pd.pdelta_linear_variants(d["X"], d["W_b"], pd.VariantSet(d["variants"], axis), out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        check_y(Y, ref, f"chunked R={R} d_in={d_in} stage={stage} axis={axis}")
+
+
+@pytest.mark.parametrize("R,d_in", [(17, 160), (4, 160), (20, 96)])
+def test_request_by_request_fallback(R, d_in):
+    # d_in not a multiple of 128: the requests run one after the other
+    d_out = 48
+    X, W_b, Bs, vs, d = make_variants(d_out, d_in, R, synth.F16, orc.COL, synth.seed_for(1, 5000 + R))
+    ref = orc.linear_variants(X, W_b, Bs, vs, orc.COL, synth.F16)
+    Y = pd.pdelta_linear_variants(d["X"], d["W_b"], pd.VariantSet(d["variants"], orc.COL), out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check_y(Y, ref, f"fallback R={R} d_in={d_in}")
+
+
+def test_identical_variants_equal_the_ordinary_layer():
+    X, W_b, Bs, vs, d = make_variants(128, 512, 6, synth.F16, orc.ROW, 77)
+    vset = pd.VariantSet([d["variants"][2]] * 6, orc.ROW)
+    Y = pd.pdelta_linear_variants(d["X"], d["W_b"], vset, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check_y(Y, orc.linear(X, W_b, Bs[2], vs[2], orc.ROW), "identical variants")
+
+
+def test_no_requests_is_a_no_op():
+    W = torch.zeros((32, 128), dtype=torch.float16, device=DEV)
+    X = torch.zeros((0, 128), dtype=torch.float16, device=DEV)
+    Y = pd.pdelta_linear_variants(X, W, pd.VariantSet([], pd.ROW))
+    assert Y.shape == (0, 32)

@@ -185,3 +185,28 @@ def test_config0_shape_runs_in_well_under_a_second():
     assert Y.shape == (4, 256) and np.isfinite(Y).all()
     # RMS(Y) ~ sqrt(d_in) * 0.02 for N(0,1) inputs against N(0, 0.02^2) weights
     assert 0.3 < np.sqrt((Y ** 2).mean()) < 0.65
+
+
+def test_variants_reduce_to_the_single_layer_and_to_brute_force():
+    # identical variants: the R requests are the R tokens of one ordinary layer
+    rng = np.random.default_rng(21)
+    d_out, d_in, R = 24, 96, 5
+    X = rng.standard_normal((R, d_in)).astype(np.float16)
+    W_b = (rng.standard_normal((d_out, d_in)) * 0.05).astype(np.float16)
+    Bs = [rng.integers(0, 2 ** 32, (d_out, d_in // 32), dtype=np.uint32) for _ in range(R)]
+    v_rows = [(rng.random(d_out) * 0.01).astype(np.float16) for _ in range(R)]
+    v_cols = [(rng.random(d_in) * 0.01).astype(np.float16) for _ in range(R)]
+    same = orc.linear_variants(X, W_b, [Bs[0]] * R, [v_rows[0]] * R, orc.ROW)
+    assert np.array_equal(same, orc.linear(X, W_b, Bs[0], v_rows[0], orc.ROW))
+    # distinct variants against the definition written out with numpy on unpacked signs
+    for axis, vs in ((orc.ROW, v_rows), (orc.COL, v_cols)):
+        got = orc.linear_variants(X, W_b, Bs, vs, axis)
+        for r in range(R):
+            S = orc.unpack(Bs[r], d_in)
+            v = vs[r].astype(np.float64)
+            W_hat = W_b.astype(np.float64) + (v[:, None] * S if axis == orc.ROW else v[None, :] * S)
+            want = X[r].astype(np.float64) @ W_hat.T
+            assert np.allclose(got[r], want, rtol=1e-12, atol=1e-12)
+    # a request's result does not depend on the other requests
+    alone = orc.linear_variants(X[2:3], W_b, [Bs[2]], [v_cols[2]], orc.COL)
+    assert np.array_equal(alone[0], orc.linear_variants(X, W_b, Bs, v_cols, orc.COL)[2])
