@@ -258,6 +258,46 @@ int pdelta_linear_ref_at(const uint16_t* X, const uint16_t* W_b, const uint32_t*
 }
 
 /* Number of threads the parallel loops above will use (for the bench's "cores" field). */
+/*
+ * Gradient of a loss with respect to the scale vector, given dY = dL/dY (algorithm "Train
+ * per-row/column scaling vectors via activation matching": the loss is backpropagated through
+ * v only).  From Eq. 1 inside the layer forward, Y[m,o] = sum_i X[m,i] (W_b[o,i] + v. B[o,i]):
+ *   row:  dL/dv[o] = sum_m dY[m,o] * sum_i X[m,i] B[o,i]
+ *   col:  dL/dv[i] = sum_m X[m,i] * sum_o dY[m,o] B[o,i]
+ * Plain loops in fp64, sums in index order.  grad has d_out (row) or d_in (col) entries.
+ */
+int pdelta_grad_v_ref(const uint16_t* X, const uint16_t* dY, const uint32_t* B_packed, int axis,
+                      int64_t M, int64_t d_out, int64_t d_in, int dtype, double* grad)
+{
+    if (!X || !dY || !B_packed || !grad || M < 0 || d_out <= 0 || d_in <= 0) return -1;
+    if (axis != 0 && axis != 1) return -1;
+    const int64_t wpr = words_per_row(d_in);
+    const int64_t n = axis == 0 ? d_out : d_in;
+#pragma omp parallel for schedule(static)
+    for (int64_t a = 0; a < n; ++a) {
+        double g = 0.0;
+        for (int64_t m = 0; m < M; ++m) {
+            if (axis == 0) {
+                double s = 0.0;
+                for (int64_t i = 0; i < d_in; ++i) {
+                    const double b = ((B_packed[a * wpr + i / 32] >> (i % 32)) & 1u) ? 1.0 : -1.0;
+                    s += pdelta_ref_decode(X[m * d_in + i], dtype) * b;
+                }
+                g += pdelta_ref_decode(dY[m * d_out + a], dtype) * s;
+            } else {
+                double t = 0.0;
+                for (int64_t o = 0; o < d_out; ++o) {
+                    const double b = ((B_packed[o * wpr + a / 32] >> (a % 32)) & 1u) ? 1.0 : -1.0;
+                    t += pdelta_ref_decode(dY[m * d_out + o], dtype) * b;
+                }
+                g += pdelta_ref_decode(X[m * d_in + a], dtype) * t;
+            }
+        }
+        grad[a] = g;
+    }
+    return 0;
+}
+
 int pdelta_ref_threads(void)
 {
 #ifdef _OPENMP

@@ -55,6 +55,7 @@ def _load():
         lib.pdelta_patch_round_ref.argtypes = [vp, vp, vp, i32, i64, i64, i32, vp]
         lib.pdelta_linear_ref.argtypes = [vp, vp, vp, vp, i32, i64, i64, i64, i32, vp]
         lib.pdelta_linear_ref_at.argtypes = [vp, vp, vp, vp, i32, i64, i64, i64, i32, i64, vp, vp, vp]
+        lib.pdelta_grad_v_ref.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, vp]
         lib.pdelta_ref_threads.restype = i32
         _lib = lib
     return _lib
@@ -189,6 +190,19 @@ def linear_at(X, W_b, B_packed, v, axis: int, m_idx, o_idx, x_dtype: int = F16) 
     _check(lib.pdelta_linear_ref_at(_ptr(x), _ptr(wb), _ptr(B), _ptr(vv), axis, x.shape[0],
                                     d_out, d_in, x_dtype, mi.size, _ptr(mi), _ptr(oi),
                                     _ptr(out)), "linear_at")
+    return out
+
+
+def grad_v(X, dY, B_packed, axis: int, dtype: int = F16) -> np.ndarray:
+    """dL/dv (fp64) for upstream gradient dY: [d_out] in row mode, [d_in] in column mode."""
+    X, dY = _bits16(X), _bits16(dY)
+    B = np.ascontiguousarray(B_packed, dtype=np.uint32)
+    M, d_in = X.shape
+    d_out = dY.shape[1]
+    assert dY.shape[0] == M and B.shape == (d_out, words_per_row(d_in))
+    out = np.empty(d_out if axis == ROW else d_in, dtype=np.float64)
+    _check(_load().pdelta_grad_v_ref(_ptr(X), _ptr(dY), _ptr(B), axis, M, d_out, d_in, dtype, _ptr(out)),
+           "pdelta_grad_v_ref")
     return out
 
 

@@ -210,3 +210,33 @@ def test_variants_reduce_to_the_single_layer_and_to_brute_force():
     # a request's result does not depend on the other requests
     alone = orc.linear_variants(X[2:3], W_b, [Bs[2]], [v_cols[2]], orc.COL)
     assert np.array_equal(alone[0], orc.linear_variants(X, W_b, Bs, v_cols, orc.COL)[2])
+
+
+def test_grad_v_is_the_slope_of_the_layer_in_v_and_matches_brute_force():
+    # Y is linear in v, so for L(v) = sum(dY * Y(v)) the gradient is an exact finite difference:
+    # dL/dv[a] = L(v + e_a) - L(v).  Integer-valued v keeps v + 1 representable in fp16.
+    rng = np.random.default_rng(31)
+    M, d_out, d_in = 7, 12, 64
+    X = rng.standard_normal((M, d_in)).astype(np.float16)
+    dY = rng.standard_normal((M, d_out)).astype(np.float16)
+    W_b = (rng.standard_normal((d_out, d_in)) * 0.05).astype(np.float16)
+    B = rng.integers(0, 2 ** 32, (d_out, d_in // 32), dtype=np.uint32)
+    S = orc.unpack(B, d_in)
+    X64, dY64 = X.astype(np.float64), dY.astype(np.float64)
+    for axis, n in ((orc.ROW, d_out), (orc.COL, d_in)):
+        g = orc.grad_v(X, dY, B, axis)
+        v = rng.integers(-3, 4, n).astype(np.float16)
+        base = float((dY64 * orc.linear(X, W_b, B, v, axis)).sum())
+        for a in (0, 1, n // 2, n - 1):
+            bumped = v.copy()
+            bumped[a] += np.float16(1.0)
+            slope = float((dY64 * orc.linear(X, W_b, B, bumped, axis)).sum()) - base
+            assert abs(slope - g[a]) <= 1e-9 * max(1.0, abs(g[a])), (axis, a)
+        # the formula written out with numpy on the unpacked signs
+        want = ((X64 @ S.T) * dY64).sum(0) if axis == orc.ROW else ((dY64 @ S) * X64).sum(0)
+        assert np.allclose(g, want, rtol=1e-12, atol=1e-12)
+    # swapping the roles of the two modes needs the transposed sign matrix: with B = all ones
+    # both gradients reduce to sums that are easy to state
+    ones = np.full((d_out, d_in // 32), 0xFFFFFFFF, dtype=np.uint32)
+    assert np.allclose(orc.grad_v(X, dY, ones, orc.ROW), (X64.sum(1)[:, None] * dY64).sum(0), atol=1e-12)
+    assert np.allclose(orc.grad_v(X, dY, ones, orc.COL), (dY64.sum(1)[:, None] * X64).sum(0), atol=1e-12)
