@@ -10,7 +10,7 @@ each with its own events, the other workloads of the path (prefill GEMM shapes, 
 decode stack, the offline pack of that stack, the in-place patch) and the CPU oracle on a
 bounded sample; they are reported as extra objects on the same JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--skip variants,prefill,stack,pack,patch,cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--skip variants,prefill,grad,stack,pack,patch,cpu]
 """
 from __future__ import annotations
 
@@ -221,6 +221,26 @@ def main() -> int:
         out["roofline_prefill"] = {"bound": "mfma", "kernel": "linear_gemm_kernel (prefill, bf16 in, fp16 MFMA)",
                                    "achieved": round(agg, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                                    "frac": round(agg / MFMA_PEAK_TFLOPS, 4), "traffic": None}
+        torch.cuda.empty_cache()
+
+    # ---------------- backward with respect to v: M = 2048 tokens, 4096 x 4096, bf16 -----------
+    if "grad" not in skip:
+        Mg, Ng, Kg = 2048, 4096, 4096
+        Xg = synth.x_device(Mg, Kg, synth.BF16, synth.seed_for(2, 70), dev)
+        dYg = synth.x_device(Mg, Ng, synth.BF16, synth.seed_for(2, 71), dev)
+        Bg = torch.randint(-2 ** 31, 2 ** 31 - 1, (Ng, Kg // 32), dtype=torch.int32, device=dev)
+        res = {"workload": "dL/dv from dY: 2048 tokens, 4096 x 4096 layer, bf16 X and dY, fp32 gradient"}
+        for name, axis in (("row", pd.ROW), ("col", pd.COL)):
+            ws = torch.empty(pd.pdelta_grad_v_workspace_bytes(Mg, Ng, Kg, axis), dtype=torch.uint8, device=dev)
+            outg = torch.empty(Ng if axis == pd.ROW else Kg, dtype=torch.float32, device=dev)
+            fn = lambda: pd.pdelta_grad_v(Xg, dYg, Bg, axis, out=outg, workspace=ws)
+            timed(fn, 3)
+            ms = timed(fn, 20) / 20
+            flop = 2.0 * Mg * Ng * Kg
+            res[name] = {"us": round(ms * 1e3, 1), "TFLOP/s": round(flop / ms / 1e9, 1),
+                         "frac_mfma": round(flop / ms / 1e9 / MFMA_PEAK_TFLOPS, 4)}
+        out["grad_v"] = res
+        del Xg, dYg, Bg
         torch.cuda.empty_cache()
 
     # ---------------- stack: 224 linears of a 7B-shaped model, batch 1 -------------------------

@@ -244,6 +244,29 @@ int pdelta_linear_variants(const void* X, const void* W_b, const pdelta_variant*
                            const pdelta_variant* variants_device, int32_t R, int axis, void* Y,
                            int64_t d_out, int64_t d_in, int x_dtype, int y_dtype, void* stream);
 
+/*
+ * Gradient of a loss with respect to the scale vector, given dY = dL/dY: the backward step of
+ * the paper's algorithm "Train per-row/column scaling vectors via activation matching", which
+ * backpropagates through v only.  From Eq. 1 inside the layer forward:
+ *   row:  grad_v[o] = sum_m dY[m,o] * sum_i X[m,i] B[o,i]
+ *   col:  grad_v[i] = sum_m X[m,i]  * sum_o dY[m,o] B[o,i]
+ * Arguments
+ *   X        in   [M, d_in],  dtype (PDELTA_F16 or PDELTA_BF16)
+ *   dY       in   [M, d_out], same dtype
+ *   B_packed in   [d_out, d_in/32] uint32
+ *   grad_v   out  fp32, [d_out] (row) or [d_in] (col); overwritten, not accumulated
+ *   workspace scratch of >= pdelta_grad_v_workspace_bytes(M, d_out, d_in, axis) bytes, 16-byte
+ *             aligned (PDELTA_EWORKSPACE otherwise); contents on entry ignored
+ * Products are exact, sums are accumulated in fp32 in a fixed order (reproducible).  Column mode
+ * needs d_out to be a multiple of 32 (PDELTA_ESHAPE): it transposes the packed signs into the
+ * workspace.  M = 0 writes zeros.
+ */
+size_t pdelta_grad_v_workspace_bytes(int64_t M, int64_t d_out, int64_t d_in, int axis);
+
+int pdelta_grad_v(const void* X, const void* dY, const uint32_t* B_packed, int axis, float* grad_v,
+                  int64_t M, int64_t d_out, int64_t d_in, int dtype, void* workspace,
+                  size_t workspace_bytes, void* stream);
+
 /* Static, human-readable name of a pdelta_status value. */
 const char* pdelta_status_string(int status);
 

@@ -80,6 +80,10 @@ def lib() -> ctypes.CDLL:
         L.pdelta_linear_variants.restype = i32
         L.pdelta_linear_variants.argtypes = [vp, vp, ctypes.POINTER(Variant), vp, ctypes.c_int32, i32, vp, i64, i64,
                                              i32, i32, vp]
+        L.pdelta_grad_v_workspace_bytes.restype = sz
+        L.pdelta_grad_v_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.pdelta_grad_v.restype = i32
+        L.pdelta_grad_v.argtypes = [vp, vp, vp, i32, vp, i64, i64, i64, i32, vp, sz, vp]
         L.pdelta_status_string.restype = ctypes.c_char_p
         L.pdelta_status_string.argtypes = [i32]
         _lib = L
@@ -349,4 +353,26 @@ def pdelta_linear_variants(X, W_b, variants: VariantSet, out=None, out_dtype=Non
                                       R, variants.axis, _dev(out, "Y") or None, d_out, d_in,
                                       dtype_code(X.dtype), dtype_code(out.dtype), _stream())
     _check(rc, "pdelta_linear_variants")
+    return out
+
+
+def pdelta_grad_v_workspace_bytes(M: int, d_out: int, d_in: int, axis: int) -> int:
+    return int(lib().pdelta_grad_v_workspace_bytes(M, d_out, d_in, axis))
+
+
+def pdelta_grad_v(X, dY, B_packed, axis: int, out=None, workspace: torch.Tensor | None = None):
+    """dL/dv (fp32) for upstream gradient dY: [d_out] in row mode, [d_in] in column mode."""
+    M, d_in = X.shape
+    d_out = dY.shape[1]
+    if dY.shape[0] != M or dY.dtype != X.dtype:
+        raise ValueError("X and dY must agree in M and dtype")
+    if out is None:
+        out = torch.empty(d_out if axis == ROW else d_in, dtype=torch.float32, device=X.device)
+    if workspace is None:
+        workspace = torch.empty(max(pdelta_grad_v_workspace_bytes(M, d_out, d_in, axis), 16), dtype=torch.uint8,
+                                device=X.device)
+    rc = lib().pdelta_grad_v(_dev(X, "X") or None, _dev(dY, "dY") or None, _dev(B_packed, "B_packed"), axis,
+                             _dev(out, "grad_v"), M, d_out, d_in, dtype_code(X.dtype), _dev(workspace, "workspace"),
+                             workspace.numel(), _stream())
+    _check(rc, "pdelta_grad_v")
     return out

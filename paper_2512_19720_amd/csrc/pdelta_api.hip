@@ -323,6 +323,38 @@ int pdelta_linear_variants(const void* X, const void* W_b, const pdelta_variant*
     return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
 }
 
+size_t pdelta_grad_v_workspace_bytes(int64_t M, int64_t d_out, int64_t d_in, int axis)
+{
+    if (M < 0 || d_out <= 0 || d_in <= 0 || (axis != PDELTA_ROW && axis != PDELTA_COL)) return 0;
+    return pdelta::grad_v_workspace_bytes(M, d_out, d_in, axis);
+}
+
+int pdelta_grad_v(const void* X, const void* dY, const uint32_t* B_packed, int axis, float* grad_v,
+                  int64_t M, int64_t d_out, int64_t d_in, int dtype, void* workspace,
+                  size_t workspace_bytes, void* stream)
+{
+    using namespace pdelta;
+    if (B_packed == nullptr || grad_v == nullptr) return PDELTA_EINVAL;
+    if (axis != PDELTA_ROW && axis != PDELTA_COL) return PDELTA_EINVAL;
+    if (M < 0) return PDELTA_EINVAL;
+    if (M > 0 && (X == nullptr || dY == nullptr)) return PDELTA_EINVAL;
+    if (const int rc = check_dims(d_out, d_in)) return rc;
+    if (M > kMaxTokens) return PDELTA_ESHAPE;
+    if (axis == PDELTA_COL && d_out % 32 != 0) return PDELTA_ESHAPE;
+    if (!is_w_dtype(dtype)) return PDELTA_EDTYPE;
+    if (workspace == nullptr || workspace_bytes < grad_v_workspace_bytes(M, d_out, d_in, axis))
+        return PDELTA_EWORKSPACE;
+    if (misaligned(X) || misaligned(dY) || misaligned(B_packed) || misaligned(grad_v) || misaligned(workspace))
+        return PDELTA_EALIGN;
+    const size_t g_bytes = (size_t)(axis == PDELTA_ROW ? d_out : d_in) * 4;
+    if (overlaps(grad_v, g_bytes, X, (size_t)M * d_in * 2) || overlaps(grad_v, g_bytes, dY, (size_t)M * d_out * 2) ||
+        overlaps(grad_v, g_bytes, B_packed, (size_t)d_out * d_in / 8) ||
+        overlaps(grad_v, g_bytes, workspace, workspace_bytes))
+        return PDELTA_EINVAL;
+    const int rc = launch_grad_v(dtype, axis, X, dY, B_packed, grad_v, M, d_out, d_in, workspace, (hipStream_t)stream);
+    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+}
+
 const char* pdelta_status_string(int status)
 {
     switch (status) {

@@ -48,6 +48,12 @@ int launch_linear_variants(int x_dtype, int y_dtype, int axis, const void* X, co
                            const ::pdelta_variant* variants_device, int R, void* Y, int64_t d_out,
                            int64_t d_in, hipStream_t stream);
 
+// dL/dv from dY (training of the scale vectors).  Workspace: partial sums per token tile, plus
+// the transposed sign bits in column mode.
+size_t grad_v_workspace_bytes(int64_t M, int64_t d_out, int64_t d_in, int axis);
+int launch_grad_v(int dtype, int axis, const void* X, const void* dY, const uint32_t* B_packed, float* grad,
+                  int64_t M, int64_t d_out, int64_t d_in, void* workspace, hipStream_t stream);
+
 // Prefill-shaped layer (many tokens): MFMA tile kernel.
 int launch_linear_gemm(int x_dtype, int y_dtype, int axis, const void* X, const void* W_b,
                        const uint32_t* B_packed, const uint16_t* v, void* Y, int64_t M,

@@ -23,7 +23,8 @@ def test_library_exports_every_declared_function():
     assert {"pdelta_pack", "pdelta_linear_row", "pdelta_linear_col", "pdelta_patch",
             "pdelta_pack_workspace_bytes", "pdelta_status_string", "pdelta_linear_batch_plan",
             "pdelta_linear_batch", "pdelta_patch_batch", "pdelta_pack_batch_plan",
-            "pdelta_pack_batch", "pdelta_linear_variants"} <= set(names)
+            "pdelta_pack_batch", "pdelta_linear_variants", "pdelta_grad_v",
+            "pdelta_grad_v_workspace_bytes"} <= set(names)
     L = pd.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -255,6 +256,35 @@ def test_linear_variants_argument_errors():
     assert run(variants(v=None)) == pd.EINVAL
     assert run(variants(v=A + 0x3000002)) == pd.EALIGN
     assert run(variants(B_packed=A + 0x4000000)) == pd.EINVAL         # Y overlaps a variant's signs
+
+
+def test_grad_v_workspace_and_argument_errors():
+    L = pd.lib()
+    # row: one fp32 partial per (256-token tile, output); col: the same per input, rounded up
+    # to 256 bytes, plus the transposed sign bits
+    assert pd.pdelta_grad_v_workspace_bytes(2048, 4096, 11008, pd.ROW) == 8 * 4096 * 4
+    assert pd.pdelta_grad_v_workspace_bytes(300, 64, 96, pd.COL) == 2 * 96 * 4 + 96 * 64 // 8
+    assert pd.pdelta_grad_v_workspace_bytes(0, 64, 96, pd.ROW) == 64 * 4
+    assert pd.pdelta_grad_v_workspace_bytes(5, 0, 96, pd.ROW) == 0
+    assert pd.pdelta_grad_v_workspace_bytes(5, 64, 96, 3) == 0
+
+    def run(X=A, dY=A + 0x1000000, B=A + 0x2000000, axis=pd.ROW, g=A + 0x3000000, M=4, d_out=64, d_in=128,
+            dt=pd.F16, ws=A + 0x4000000, wsb=1 << 20):
+        return L.pdelta_grad_v(X, dY, B, axis, g, M, d_out, d_in, dt, ws, wsb, None)
+
+    for null in ("X", "dY", "B", "g"):
+        assert run(**{null: None}) == pd.EINVAL
+    assert run(axis=2) == pd.EINVAL
+    assert run(M=-1) == pd.EINVAL
+    assert run(d_in=100) == pd.ESHAPE
+    assert run(axis=pd.COL, d_out=48) == pd.ESHAPE                    # column mode transposes 32-bit words
+    assert run(dt=pd.F32) == pd.EDTYPE
+    assert run(ws=None) == pd.EWORKSPACE
+    assert run(wsb=64 * 4 - 1) == pd.EWORKSPACE
+    for name in ("X", "dY", "B", "g", "ws"):
+        assert run(**{name: A + 0x5000008}) == pd.EALIGN
+    assert run(g=A + 16) == pd.EINVAL                                 # inside X
+    assert run(g=A + 0x4000000) == pd.EINVAL                          # inside the workspace
 
 
 def call_pack(Wf=A, Wb=A + 0x1000000, d_out=64, d_in=128, dt=pd.F16, B=A + 0x2000000,
