@@ -141,7 +141,7 @@ def main() -> int:
                 traffic = int(float(line.split(":", 1)[1].split()[0]))
     launches = args.steps * len(cases)
     avg_launch_us = ms_total * 1e3 / launches
-    roofline = {"bound": "hbm", "kernel": "linear_skinny_kernel (decode, 4096x4096 fp16)",
+    roofline = {"bound": "hbm", "kernel": "linear_skinny_staged_kernel (decode, 4096x4096 fp16)",
                 "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(value / HBM_PEAK_GBS, 4),
                 "bytes_per_launch": step_bytes // len(cases),
@@ -377,7 +377,7 @@ def main() -> int:
         from oracle import pdelta_oracle as orc
         L = synth.layer_host(N, K, 16, synth.F16, "row", synth.seed_for(1, 0))
         Bo, vr, vc = orc.pack(L["dW"], np.zeros_like(L["dW"]))
-        reps = 3
+        reps = 12
         t0 = time.perf_counter()
         for _ in range(reps):
             for axis, M in cases:
