@@ -148,9 +148,9 @@ int pdelta_patch(const void* W_b, const uint32_t* B_packed, const uint16_t* v, i
  * to device memory and passes both copies: the host copy is read for validation and launch
  * geometry, the device copy by the kernel.  Editing pointers later needs no new plan as long
  * as shapes and axes stay the same (copy the array again).
- * When the layers do not fit the batched decode kernel (M > 16, d_in not a multiple of 128, or
- * operand slabs too large for LDS) the call launches them one by one in order, with the same
- * results.  M = 0 or n_layers = 0 is a no-op.
+ * When the layers do not fit the batched decode kernel (M > 16, a d_in that is not a multiple of
+ * 128, or a sign slab too large for LDS) the call launches them one by one in order, with the
+ * same results.  M = 0 or n_layers = 0 is a no-op.
  * Ownership and errors: layers_host is host memory, layers_device device memory holding the
  * same n_layers descriptors (16-byte aligned, PDELTA_EALIGN); both stay the caller's and must
  * stay valid until the stream has run the call.  Each layer is checked like a single-layer call

@@ -388,7 +388,7 @@ linear_skinny_staged_kernel(const uint16_t* __restrict__ X, const uint16_t* __re
 // Workgroup b belongs to the last layer whose first_block is <= b.  One launch instead of one
 // per layer removes the per-kernel ramp-up and drain (about 2.4 us each on MI355X, a third of a
 // 4096 x 4096 decode layer) for layers that do not depend on each other.
-template <int XDT, int WAVES, int DEPTH>
+template <int XDT, int WAVES, int DEPTH, bool STAGE_X>
 __global__ void __launch_bounds__(WAVES * 64)
 linear_skinny_batch_kernel(const pdelta_layer* __restrict__ layers, int n_layers, int M, int y_dtype)
 {
@@ -401,10 +401,10 @@ linear_skinny_batch_kernel(const pdelta_layer* __restrict__ layers, int n_layers
     const pdelta_layer L = layers[lo];
     const int block = b - L.first_block;
     if (L.axis == 0)
-        staged_body<XDT, 0, WAVES, DEPTH, true>((const uint16_t*)L.X, (const uint16_t*)L.W_b, L.B_packed,
+        staged_body<XDT, 0, WAVES, DEPTH, STAGE_X>((const uint16_t*)L.X, (const uint16_t*)L.W_b, L.B_packed,
                                                 L.v, L.Y, M, (int)L.d_out, (int)L.d_in, y_dtype, block);
     else
-        staged_body<XDT, 1, WAVES, DEPTH, true>((const uint16_t*)L.X, (const uint16_t*)L.W_b, L.B_packed,
+        staged_body<XDT, 1, WAVES, DEPTH, STAGE_X>((const uint16_t*)L.X, (const uint16_t*)L.W_b, L.B_packed,
                                                 L.v, L.Y, M, (int)L.d_out, (int)L.d_in, y_dtype, block);
 }
 
@@ -512,21 +512,28 @@ int launch_linear_skinny_batch(int x_dtype, int y_dtype, const pdelta_layer* lay
                                const pdelta_layer* layers_device, int n_layers, int64_t M,
                                hipStream_t stream)
 {
-    // applicable when every layer can use the staged kernel with X in LDS
+    // applicable when every layer can use the staged kernel (sign slab in LDS); X goes to LDS too
+    // when it is small enough in every layer, else all layers read it through L2
     if (M > 16 || tune_value("skinny_batch", 1) == 0) return 1;
+    bool stage_x = true;
+    for (int l = 0; l < n_layers; ++l) {
+        const pdelta_layer& L = layers_host[l];
+        if (L.d_in % 128 != 0) return 1;
+        if (M * L.d_in > 24576 || staged_lds_bytes(8, L.axis, true, M, L.d_in) == 0) stage_x = false;
+    }
     int64_t total = 0;
     size_t lds = 0;
     for (int l = 0; l < n_layers; ++l) {
         const pdelta_layer& L = layers_host[l];
-        if (L.d_in % 128 != 0 || M * L.d_in > 24576) return 1;
-        const size_t need = staged_lds_bytes(8, L.axis, true, M, L.d_in);
+        const size_t need = staged_lds_bytes(8, L.axis, stage_x, M, L.d_in);
         if (need == 0) return 1;
         if (need > lds) lds = need;
         total += (L.d_out + 15) / 16;
     }
     if (total > 0x7FFFFFFF) return 1;
-    auto kernel = x_dtype == kBF16 ? linear_skinny_batch_kernel<kBF16, 8, 2>
-                                   : linear_skinny_batch_kernel<kF16, 8, 2>;
+    void (*kernel)(const pdelta_layer*, int, int, int);
+    if (x_dtype == kBF16) kernel = stage_x ? linear_skinny_batch_kernel<kBF16, 8, 2, true> : linear_skinny_batch_kernel<kBF16, 8, 2, false>;
+    else kernel = stage_x ? linear_skinny_batch_kernel<kF16, 8, 2, true> : linear_skinny_batch_kernel<kF16, 8, 2, false>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)kStagedLdsLimit) != hipSuccess)

@@ -61,7 +61,7 @@ def test_batched_kernel_mixed_shapes_and_axes(M, dtype):
     (17, MIXED),                                                   # M above the batched kernel's 16 tokens
     (100, MIXED[:3]),                                              # prefill path, layer by layer
     (2, [(64, 160, orc.ROW), (48, 256, orc.COL)]),                 # d_in not a multiple of 128
-    (16, [(32, 4096, orc.COL), (32, 256, orc.ROW)]),               # X slab too large for LDS
+    (16, [(32, 4096, orc.COL), (32, 256, orc.ROW)]),               # X too large for LDS: the batched kernel reads it through L2
 ])
 def test_layer_by_layer_fallback_gives_the_same_results(M, shapes):
     cases, plan = build_batch(shapes, M, synth.F16, synth.seed_for(3, 600 + M), torch.float32)
