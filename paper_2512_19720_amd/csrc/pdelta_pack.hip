@@ -13,7 +13,7 @@
 //
 // Exact sums.  fp16 values are integer multiples of 2^-24 below 2^16, so W_f - W_b is exact in
 // fp64 and every |dW| * 2^24 is an integer below 2^41.  A workgroup adds at most 1024 of them
-// per row and 64 per column in fp64 (below 2^51 units: still exact).  The finalize kernel
+// per row and 512 per column in fp64 (below 2^51 units: still exact).  The finalize kernel
 // converts each partial to uint64 units of 2^-24 and adds integers.  bf16 has no such grid; its
 // partials are added in fp64 and are exact only while fp64 holds them exactly.
 #include <type_traits>
@@ -374,8 +374,9 @@ static int launch_pack(const void* W_f, const void* W_b, int64_t d_out, int64_t 
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-// Tiles of a job in the batched kernels: 4 waves x tile_blocks blocks of 8 rows, 1024 columns.
-int pack_batch_tile_blocks(int64_t d_out) { return d_out >= 512 ? 4 : 2; }
+// Tiles of a job in the batched kernels: 4 waves x tile_blocks blocks of 8 rows, 1024 columns
+// (512-row tiles for tall layers: fewest column partials, measured 5 % faster than 128 rows).
+int pack_batch_tile_blocks(int64_t d_out) { return d_out >= 2048 ? 16 : (d_out >= 512 ? 4 : 2); }
 int64_t pack_batch_tiles(int64_t d_out, int64_t d_in, int tile_blocks)
 {
     const int64_t tile_rows = 32 * tile_blocks;

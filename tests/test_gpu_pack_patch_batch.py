@@ -14,7 +14,8 @@ pytestmark = pytest.mark.gpu
 
 # ragged rows and columns around the 64/128-row and 1024-column tiles, a one-row layer, a layer
 # with d_in % 128 != 0 (sign rows not 16-byte aligned), layers on both sides of the 512-row rule
-SHAPES = [(256, 512), (1, 32), (33, 96), (100, 1056), (70, 2048 + 160), (515, 1024), (640, 2080), (129, 4096)]
+SHAPES = [(256, 512), (1, 32), (33, 96), (100, 1056), (70, 2048 + 160), (515, 1024), (640, 2080), (129, 4096),
+          (2100, 1184)]          # tall layer: 512-row tiles, ragged last tile
 
 
 @pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
