@@ -465,11 +465,14 @@ static int try_staged(const void* X, const void* W_b, const uint32_t* B_packed, 
     // layer is wide (d_in >= 8192) but has few workgroups (<= 2 per CU) 16 waves fill the CU better.
     const bool wide_few = d_in >= 8192 && (d_out + 15) / 16 <= 512;
     const int waves = tune_value("stg_waves", wide_few ? 16 : 8);
-    const int depth = tune_value("stg_depth", 2);
     const bool want_x = tune_value("stg_x", 1) != 0;
     size_t lds = want_x ? staged_lds_bytes(waves, AXIS, true, M, d_in) : 0;
     const bool stage_x = lds != 0 && M * d_in <= 24576;
     if (!stage_x) lds = staged_lds_bytes(waves, AXIS, false, M, d_in);
+    // Row mode, small batch, exactly four steps per wave (d_in = 4096 at 8 waves): all four in
+    // flight from the start is 3 % faster than a ring of two (same-run A/B); elsewhere it makes no
+    // difference or loses (column mode and larger batches carry more registers per step).
+    const int depth = tune_value("stg_depth", (AXIS == 0 && stage_x && d_in / 128 == 4 * waves) ? 4 : 2);
     if (lds == 0) return 1;
 #define PDELTA_STG(WAVES, DEPTH)                                                                        \
     return stage_x ? launch_staged<XDT, AXIS, WAVES, DEPTH, true>(X, W_b, B_packed, v, Y, M, d_out, d_in, \
