@@ -5,7 +5,9 @@ One timed "step" = the decode workload of the 4096 x 4096 fp16 layer: row and co
 batch 1 and batch 16 (four launches), each launch on a different (W_b, B, v) buffer set so that
 it streams from HBM rather than from the 256 MB memory-side cache.  `value` is the effective
 bandwidth of those K steps: algorithmic bytes (every weight, sign word, scale, X and Y once)
-divided by wall time between two events on the launching stream.  The same process then times,
+divided by the time between two events on the launching stream around the replay of a HIP
+graph that holds exactly those K steps (a call through the Python binding costs about as much
+host time as a decode kernel runs).  The same process then times,
 each with its own events, the other workloads of the path (prefill GEMM shapes, the 224-linear
 decode stack, the offline pack of that stack, the in-place patch) and the CPU oracle on a
 bounded sample; they are reported as extra objects on the same JSON line.
