@@ -6,8 +6,8 @@ batch 1 and batch 16 (four launches), each launch on a different (W_b, B, v) buf
 it streams from HBM rather than from the 256 MB memory-side cache.  `value` is the effective
 bandwidth of those K steps: algorithmic bytes (every weight, sign word, scale, X and Y once)
 divided by the time between two events on the launching stream around the replay of a HIP
-graph that holds exactly those K steps (a call through the Python binding costs about as much
-host time as a decode kernel runs).  The same process then times,
+graph that holds exactly those K steps (a call through the Python binding costs host time of the
+order of a decode kernel's run time).  The same process then times,
 each with its own events, the other workloads of the path (prefill GEMM shapes, the 224-linear
 decode stack, the offline pack of that stack, the in-place patch) and the CPU oracle on a
 bounded sample; they are reported as extra objects on the same JSON line.
@@ -118,8 +118,8 @@ def main() -> int:
 
     def graph_of(fn, iters):
         """The launches of `iters` calls of fn recorded into one HIP graph (the library records
-        plain kernel nodes only).  The Python binding needs about 8 us of host time per call,
-        about as long as a decode kernel runs, so launching from Python would time the host."""
+        plain kernel nodes only).  The Python binding needs 5 us and more of host time per call,
+        of the order of a decode kernel's 9 us, so launching from Python can end up timing the host."""
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):

@@ -100,7 +100,15 @@ def dtype_code(t: torch.dtype) -> int:
     raise TypeError(f"unsupported dtype {t}")
 
 
+try:                                       # raw current-stream handle without building a Stream object
+    _raw_stream = torch._C._cuda_getCurrentRawStream
+except AttributeError:                     # pragma: no cover - older torch
+    _raw_stream = None
+
+
 def _stream() -> int:
+    if _raw_stream is not None:
+        return _raw_stream(torch.cuda.current_device())
     return torch.cuda.current_stream().cuda_stream
 
 
@@ -144,6 +152,9 @@ def pdelta_pack(W_f: torch.Tensor, W_b: torch.Tensor, want_row: bool = True, wan
     return B, v_row, v_col
 
 
+_DTYPE_CODE = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
+
+
 def _linear(fn_name: str, X, W_b, B_packed, v, out, out_dtype):
     M, d_in = X.shape
     d_out = W_b.shape[0]
@@ -151,10 +162,11 @@ def _linear(fn_name: str, X, W_b, B_packed, v, out, out_dtype):
         raise ValueError("X and W_b must agree in d_in and dtype")
     if out is None:
         out = torch.empty((M, d_out), dtype=out_dtype or X.dtype, device=X.device)
-    rc = getattr(lib(), fn_name)(_dev(X, "X"), _dev(W_b, "W_b"), _dev(B_packed, "B_packed"),
-                                 _dev(v, "v"), _dev(out, "Y"), M, d_out, d_in,
-                                 dtype_code(X.dtype), dtype_code(out.dtype), _stream())
-    _check(rc, fn_name)
+    fn = getattr(_lib, fn_name) if _lib is not None else getattr(lib(), fn_name)
+    rc = fn(_dev(X, "X"), _dev(W_b, "W_b"), _dev(B_packed, "B_packed"), _dev(v, "v"), _dev(out, "Y"),
+            M, d_out, d_in, _DTYPE_CODE[X.dtype], _DTYPE_CODE[out.dtype], _stream())
+    if rc != OK:
+        raise PdeltaError(rc, fn_name)
     return out
 
 
