@@ -259,10 +259,29 @@ staged_body(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
     const int n0 = block * 16;
     const int o = min(n0 + n, d_out - 1);
 
-    const uint16_t* wrow = W_b + (int64_t)o * K + g * 8;
+    // When X is not staged (larger batches) the loads of W_b and X use a lane mapping in which
+    // four consecutive lanes read 64 consecutive bytes of one row (lane = 4 row + chunk), so that
+    // the texture unit merges them into one L1 access; the MFMA wants lane = 16 chunk + row, and
+    // a lane permutation (ds_bpermute, LDS crossbar only) puts each 16 bytes where it belongs.
+    // In the MFMA's own mapping every lane is its own 16-byte L1 access, and with X as large as
+    // the W_b slab the L1 was the limit (measured: TA busy 64 % of the kernel, stalled by the
+    // cache for 47 %): -8 % row, -13 % col at M = 16 on 4096 x 4096, -28 % on 4096 x 11008 col.
+    // At small batches W_b alone does not load the L1 and the extra hop costs 5-10 %, so there
+    // the loads use the MFMA mapping directly.
+    constexpr bool COAL = !STAGE_X;
+    const int ln = COAL ? lane >> 2 : n, lg = COAL ? lane & 3 : g;   // load mapping: row / token, chunk
+    const int perm = (n * 4 + g) * 4;                 // byte address of the lane that loaded (n, g)
+    const uint16_t* wrow = W_b + (int64_t)min(n0 + ln, d_out - 1) * K + lg * 8;
     const int tok = min(n, M - 1);                    // A operand: lane % 16 = token (clamped, see above)
-    const uint16_t* xrow = X + (int64_t)tok * K + g * 8;
+    const uint16_t* xrow = X + (int64_t)min(ln, M - 1) * K + lg * 8;
     const uint16_t* vcol = v + g * 8;
+    auto to_mfma_layout = [&](uint4v a) {
+        if constexpr (!COAL) return a;
+        uint4v r;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) r[p] = (uint32_t)__builtin_amdgcn_ds_bpermute(perm, (int)a[p]);
+        return r;
+    };
 
     auto load = [&](StagedStep<AXIS, STAGE_X>& r, int kb) {
 #pragma unroll
@@ -330,9 +349,10 @@ staged_body(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
                 xa = *(const uint4v*)(my_x + kb + j * 32);
                 if constexpr (AXIS == 1) xs = *(const uint4v*)(my_xv + kb + j * 32);
             } else {
-                xa = r.x[j];
+                xa = to_mfma_layout(r.x[j]);
                 if constexpr (AXIS == 1) xs = scale_x<XDT>(xa, r.vc[j]);
             }
+            const uint4v wj = to_mfma_layout(r.w[j]);
             uint4v sg;
             if constexpr (STAGE_X) {                  // measured: the table wins at small batches (-6 %
                                                       // at M = 1), the vector ALU at M = 16
@@ -343,7 +363,7 @@ staged_body(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
             } else {
                 sg = expand_signs<(AXIS == 0 ? XDT : kF16)>(byte);
             }
-            accb = mfma16<XDT>(xa, r.w[j], accb);
+            accb = mfma16<XDT>(xa, wj, accb);
             if constexpr (AXIS == 0) accs = mfma16<XDT>(xa, sg, accs);
             else accs = mfma16<kF16>(xs, sg, accs);
         }
