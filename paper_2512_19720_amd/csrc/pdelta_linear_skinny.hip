@@ -96,26 +96,41 @@ __device__ __forceinline__ void skinny_load(SkinnyStep<MT, AXIS>& r, const uint1
     }
 }
 
+// W_b and X arrive in the load mapping (lane = 4 row + chunk: four lanes share one L1 access) and
+// are moved to the MFMA mapping (lane = 16 chunk + row) by a lane permutation; `perm` is the
+// byte address of the lane that loaded this lane's operand.
+__device__ __forceinline__ uint4v lanes_to_mfma(uint4v a, int perm)
+{
+    uint4v r;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) r[p] = (uint32_t)__builtin_amdgcn_ds_bpermute(perm, (int)a[p]);
+    return r;
+}
+
 template <int XDT, int MT, int AXIS>
-__device__ __forceinline__ void skinny_compute(const SkinnyStep<MT, AXIS>& r, int g,
+__device__ __forceinline__ void skinny_compute(const SkinnyStep<MT, AXIS>& r, int g, int perm,
                                                float4v (&accb)[MT], float4v (&accs)[MT])
 {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint32_t byte = (r.sw[j] >> (g * 8)) & 0xFFu;
+        const uint4v wj = lanes_to_mfma(r.w[j], perm);
+        uint4v xj[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) xj[mt] = lanes_to_mfma(r.x[mt][j], perm);
         if constexpr (AXIS == 0) {
             const uint4v s = expand_signs<XDT>(byte);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                accb[mt] = mfma16<XDT>(r.x[mt][j], r.w[j], accb[mt]);
-                accs[mt] = mfma16<XDT>(r.x[mt][j], s, accs[mt]);
+                accb[mt] = mfma16<XDT>(xj[mt], wj, accb[mt]);
+                accs[mt] = mfma16<XDT>(xj[mt], s, accs[mt]);
             }
         } else {
             const uint4v s = expand_signs<kF16>(byte);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                accb[mt] = mfma16<XDT>(r.x[mt][j], r.w[j], accb[mt]);
-                accs[mt] = mfma16<kF16>(scale_x<XDT>(r.x[mt][j], r.vc[j]), s, accs[mt]);
+                accb[mt] = mfma16<XDT>(xj[mt], wj, accb[mt]);
+                accs[mt] = mfma16<kF16>(scale_x<XDT>(xj[mt], r.vc[j]), s, accs[mt]);
             }
         }
     }
@@ -136,7 +151,9 @@ linear_skinny_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict_
     const int o = min(n0 + n, d_out - 1);             // rows past the end repeat the last one
     const int K = d_in;
 
-    const uint16_t* wrow = W_b + (int64_t)o * K + g * 8;
+    const int ln = lane >> 2, lg = lane & 3;          // load mapping of W_b and X: row / token, chunk
+    const int perm = (n * 4 + g) * 4;
+    const uint16_t* wrow = W_b + (int64_t)min(n0 + ln, d_out - 1) * K + lg * 8;
     const uint32_t* brow = B_packed + (int64_t)o * (K >> 5);
     const uint16_t* vcol = AXIS == 1 ? v + g * 8 : nullptr;
     const uint16_t* xrow[MT];
@@ -146,8 +163,8 @@ linear_skinny_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict_
         // MFMA output rows are independent and those rows are never stored, and a load that
         // every lane performs keeps the loop free of divergent branches and of the waits on
         // all outstanding loads that come with them.
-        const int t = min(mt * 16 + n, M - 1);
-        xrow[mt] = X + (int64_t)t * K + g * 8;
+        const int t = min(mt * 16 + ln, M - 1);
+        xrow[mt] = X + (int64_t)t * K + lg * 8;
     }
 
     float vr = 1.0f;                                  // row scale: fetched with the first loads
@@ -174,23 +191,23 @@ linear_skinny_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict_
         for (; i + 2 * DEPTH <= mine; i += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                skinny_compute<XDT, MT, AXIS>(buf[d], g, accb, accs);
+                skinny_compute<XDT, MT, AXIS>(buf[d], g, perm, accb, accs);
                 skinny_load<MT, AXIS, K128>(buf[d], wrow, brow, xrow, vcol, kb_of(i + DEPTH + d), K);
             }
         }
         const int rest = mine - i - DEPTH;            // loads still to issue, 0 <= rest < DEPTH
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
-            skinny_compute<XDT, MT, AXIS>(buf[d], g, accb, accs);
+            skinny_compute<XDT, MT, AXIS>(buf[d], g, perm, accb, accs);
             if (d < rest) skinny_load<MT, AXIS, K128>(buf[d], wrow, brow, xrow, vcol, kb_of(i + DEPTH + d), K);
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
-            if (d < rest) skinny_compute<XDT, MT, AXIS>(buf[d], g, accb, accs);
+            if (d < rest) skinny_compute<XDT, MT, AXIS>(buf[d], g, perm, accb, accs);
     } else {
         for (int i = 0; i < mine; ++i) {              // fewer steps than the ring is deep
             skinny_load<MT, AXIS, K128>(buf[0], wrow, brow, xrow, vcol, kb_of(i), K);
-            skinny_compute<XDT, MT, AXIS>(buf[0], g, accb, accs);
+            skinny_compute<XDT, MT, AXIS>(buf[0], g, perm, accb, accs);
         }
     }
 
