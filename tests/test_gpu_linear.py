@@ -123,3 +123,31 @@ def test_config2_prefill_full_size_sampled_outputs(shape, kernel, monkeypatch):
         Y = gpu_linear(orc.ROW, X, Ld["W_b"], B, v_row, yd)
         got = Y[torch.from_numpy(m_idx).to(DEV), torch.from_numpy(o_idx).to(DEV)].reshape(1, -1)
         check_y(got, ref.reshape(1, -1), f"config2 {shape} y={yd}")
+
+
+@pytest.mark.parametrize("d_out,d_in,M", [(8192, 28672, 4), (50304, 4096, 16), (8192, 28672, 300)])
+def test_very_large_layers_sampled(d_out, d_in, M):
+    """Shapes of a 70B-class MLP and of a vocabulary head (up to 470 MB of weights): pack, both
+    linear modes and patch, each checked on sampled rows / outputs that the oracle computes from
+    exactly the rows it needs."""
+    Ld = synth.layer_device(d_out, d_in, synth.F16, "row", 99, DEV)
+    X = synth.x_device(M, d_in, synth.F16, 100, DEV)
+    B, v_row, v_col = pd.pdelta_pack(Ld["dW"], torch.zeros_like(Ld["dW"]))
+    rng = np.random.default_rng(1)
+    m_idx = rng.integers(0, M, 200)
+    o_idx = np.concatenate([rng.integers(0, d_out, 196), [0, 1, d_out - 2, d_out - 1]])
+    rows = np.unique(o_idx)
+    Wb_rows = synth.torch_to_bits(Ld["W_b"][rows])
+    dW_rows = synth.torch_to_bits(Ld["dW"][rows])
+    Bo, vo, _ = orc.pack(dW_rows, np.zeros_like(dW_rows), orc.F16)
+    assert np.array_equal(words_host(B[rows]), Bo)
+    assert np.array_equal(synth.torch_to_bits(v_row[rows]), vo)
+    Xh = synth.torch_to_bits(X)
+    for axis, v_dev, v_host in ((orc.ROW, v_row, vo), (orc.COL, v_col, synth.torch_to_bits(v_col))):
+        ref = orc.linear_at(Xh, Wb_rows, Bo, v_host, axis, m_idx, np.searchsorted(rows, o_idx), orc.F16)
+        Y = gpu_linear(axis, X, Ld["W_b"], B, v_dev, torch.float32)
+        got = Y[torch.from_numpy(m_idx).to(DEV), torch.from_numpy(o_idx).to(DEV)].reshape(1, -1)
+        check_y(got, ref.reshape(1, -1), f"large {d_out}x{d_in} M={M} axis={axis}")
+    out = pd.pdelta_patch(Ld["W_b"], B, v_row, pd.ROW)
+    torch.cuda.synchronize()
+    assert np.array_equal(synth.torch_to_bits(out[rows]), orc.patch_round(Wb_rows, Bo, vo, orc.ROW))
