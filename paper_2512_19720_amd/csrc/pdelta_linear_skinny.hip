@@ -501,10 +501,13 @@ static int try_staged(const void* X, const void* W_b, const uint32_t* B_packed, 
     // Measured on MI355X: 8 waves with 2 steps in flight each is the best general choice; when a
     // layer is wide (d_in >= 8192) but has few workgroups (<= 2 per CU) 16 waves fill the CU better.
     const bool wide_few = d_in >= 8192 && (d_out + 15) / 16 <= 512;
-    const int waves = tune_value("stg_waves", wide_few ? 16 : 8);
+    // (not in column mode with X read through L2: that variant needs more than the 128 registers
+    // a 16-wave workgroup leaves per lane and spills - measured 37 us against 24 us with 8 waves)
+    const bool x_small = M * d_in <= 24576;
+    const int waves = tune_value("stg_waves", wide_few && (AXIS == 0 || x_small) ? 16 : 8);
     const bool want_x = tune_value("stg_x", 1) != 0;
     size_t lds = want_x ? staged_lds_bytes(waves, AXIS, true, M, d_in) : 0;
-    const bool stage_x = lds != 0 && M * d_in <= 24576;
+    const bool stage_x = lds != 0 && x_small;
     if (!stage_x) lds = staged_lds_bytes(waves, AXIS, false, M, d_in);
     // Row mode, small batch, exactly four steps per wave (d_in = 4096 at 8 waves): all four in
     // flight from the start is 3 % faster than a ring of two (same-run A/B); elsewhere it makes no
