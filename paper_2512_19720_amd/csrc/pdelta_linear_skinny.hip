@@ -504,7 +504,8 @@ static int try_staged(const void* X, const void* W_b, const uint32_t* B_packed, 
     // (not in column mode with X read through L2: that variant needs more than the 128 registers
     // a 16-wave workgroup leaves per lane and spills - measured 37 us against 24 us with 8 waves)
     const bool x_small = M * d_in <= 24576;
-    const int waves = tune_value("stg_waves", wide_few && (AXIS == 0 || x_small) ? 16 : 8);
+    const bool col16_ok = x_small && staged_lds_bytes(16, AXIS, true, M, d_in) != 0;   // X fits LDS at 16 waves
+    const int waves = tune_value("stg_waves", wide_few && (AXIS == 0 || col16_ok) ? 16 : 8);
     const bool want_x = tune_value("stg_x", 1) != 0;
     size_t lds = want_x ? staged_lds_bytes(waves, AXIS, true, M, d_in) : 0;
     const bool stage_x = lds != 0 && x_small;
