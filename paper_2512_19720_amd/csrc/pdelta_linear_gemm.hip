@@ -475,6 +475,166 @@ static int launch_gemm_pipe(const void* X, const void* W_b, const uint32_t* B_pa
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Small-tile variant for grids that the 256 x 128 tile cannot fill (a few hundred tokens): a
+// workgroup of 4 waves owns 64 tokens x 64 outputs, so even 256 tokens x 4096 outputs give one
+// workgroup per CU.  With so few tiles the run time of the big-tile kernels is the d_in / 64
+// sequential steps times the latency of one step (load, convert, barrier: over a microsecond),
+// whatever the batch.  Here a step's operands are 16 bytes of X and of W_b per thread, which
+// leaves registers for a ring of DEPTH steps in flight: the loads of step s + DEPTH are issued
+// while step s is multiplied, and a step costs its LDS traffic and barrier only.
+// Requires d_in % 64 == 0.
+struct SmallRegs {
+    uint4v xg[2], wg[2], vcg;
+    uint32_t sb[2];
+};
+
+template <int XDT, int AXIS, int DEPTH>
+__global__ void __launch_bounds__(256, 2)
+linear_gemm_small_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
+                         const uint32_t* __restrict__ B_packed, const uint16_t* __restrict__ v,
+                         void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype, int m_tiles,
+                         int n_tiles)
+{
+    constexpr int BM = 64, BN = 64, ROWS = 32, Q = 2;
+    constexpr int XS = BM * kGemmLDK, STAGE = (BM + BN) * kGemmLDK;               // halves
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * STAGE];              // 36,864 bytes
+
+    const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+    const int tile_n = (local / m_tiles) * kXcds + xcd;
+    const int tile_m = local % m_tiles;
+    if (tile_n >= n_tiles) return;       // whole workgroup
+    const int n0 = tile_n * BN, m0 = tile_m * BM;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int K = d_in;
+
+    const int ld_row = tid >> 3, ld_c = (tid & 7) * 8;
+    const char* xbase = (const char*)(X + (int64_t)m0 * K);
+    const char* wbase = (const char*)(W_b + (int64_t)n0 * K);
+    const char* sbase = (const char*)B_packed + (((int64_t)n0 * K) >> 3);
+    uint32_t xoff[Q], woff[Q], soff[Q], vabs_row[Q], vneg_row[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int xr = min(m0 + ld_row + ROWS * q, M - 1) - m0;
+        xoff[q] = ((uint32_t)xr * (uint32_t)K + (uint32_t)ld_c) * 2u;
+        const int wr = min(n0 + ld_row + ROWS * q, d_out - 1) - n0;
+        woff[q] = ((uint32_t)wr * (uint32_t)K + (uint32_t)ld_c) * 2u;
+        soff[q] = (uint32_t)wr * (uint32_t)(K >> 3) + (uint32_t)(tid & 7);
+        if constexpr (AXIS == 0) {
+            const uint32_t h = v[n0 + wr];
+            const uint32_t a = h & 0x7FFFu;
+            vabs_row[q] = a | (a << 16);
+            vneg_row[q] = (h & 0x8000u) ? 0xFFu : 0u;
+        }
+    }
+
+    auto load_global = [&](SmallRegs& G, int step) {
+        const int kb = step * kGemmBK;
+        const char* xb = xbase + (int64_t)kb * 2;
+        const char* wb = wbase + (int64_t)kb * 2;
+        const char* sp = sbase + (kb >> 3);
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            G.xg[q] = *(const uint4v*)(xb + xoff[q]);
+            G.wg[q] = *(const uint4v*)(wb + woff[q]);
+            G.sb[q] = (uint32_t) * (const uint8_t*)(sp + soff[q]);
+        }
+        if constexpr (AXIS == 1) G.vcg = *(const uint4v*)(v + kb + ld_c);
+    };
+    auto convert = [&](const SmallRegs& G, uint16_t* stage) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            *(uint4v*)(stage + (ld_row + ROWS * q) * kGemmLDK + ld_c) = to_f16x8<XDT>(G.xg[q]);
+            const uint4v w16 = to_f16x8<XDT>(G.wg[q]);
+            uint4v what;
+            if constexpr (AXIS == 0) {
+                const uint32_t aa = vabs_row[q];
+                what = add_signed_scale(w16, ~G.sb[q] ^ vneg_row[q], (uint4v){aa, aa, aa, aa});
+            } else {
+                uint32_t vsign = 0;
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const uint32_t vp = G.vcg[p];
+                    vsign |= ((vp >> 15) & 1u) << (2 * p) | ((vp >> 31) & 1u) << (2 * p + 1);
+                }
+                what = add_signed_scale(w16, ~G.sb[q] ^ vsign, G.vcg);
+            }
+            *(uint4v*)(stage + XS + (ld_row + ROWS * q) * kGemmLDK + ld_c) = what;
+        }
+    };
+
+    float16v acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+    const int a_off = (wm * 32 + frag_row) * kGemmLDK + frag_k;
+    const int b_off = XS + (wn * 32 + frag_row) * kGemmLDK + frag_k;
+    auto multiply = [&](const uint16_t* rd) {
+        half8 a[4], b[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            a[ks] = *(const half8*)(rd + a_off + ks * 16);
+            b[ks] = *(const half8*)(rd + b_off + ks * 16);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks], b[ks], acc, 0, 0, 0);
+    };
+
+    const int n_steps = K / kGemmBK;
+    SmallRegs G[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) load_global(G[d], min(d, n_steps - 1));
+    convert(G[0], lds);
+    __syncthreads();
+    // Every iteration refills the slot it has just consumed with step s + DEPTH (clamped to the
+    // last step near the end: a redundant load of valid memory keeps every load unconditional).
+    for (int s0 = 0; s0 < n_steps; s0 += DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            const int s = s0 + d;
+            load_global(G[d], min(s + DEPTH, n_steps - 1));
+            __builtin_amdgcn_sched_barrier(0);
+            if (s < n_steps) {                                        // workgroup-uniform
+                uint16_t* rd = lds + (s & 1) * STAGE;
+                uint16_t* wr = lds + ((s + 1) & 1) * STAGE;
+                multiply(rd);
+                if (s + 1 < n_steps) convert(G[(d + 1) % DEPTH], wr);
+            }
+            __syncthreads();
+        }
+    }
+
+    const int o = n0 + wn * 32 + (lane & 31);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int tok = m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        if (tok < M && o < d_out) {
+            const int64_t yi = (int64_t)tok * d_out + o;
+            if (y_dtype == kF32) store_y<kF32>(Y, yi, acc[r]);
+            else if (y_dtype == kBF16) store_y<kBF16>(Y, yi, acc[r]);
+            else store_y<kF16>(Y, yi, acc[r]);
+        }
+    }
+}
+
+template <int XDT, int AXIS>
+static int launch_gemm_small(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
+                             void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
+                             hipStream_t stream)
+{
+    const int m_tiles = (int)((M + 63) / 64), n_tiles = (int)((d_out + 63) / 64);
+    const int n_groups = (n_tiles + kXcds - 1) / kXcds;
+    const dim3 grid((unsigned)((int64_t)n_groups * kXcds * m_tiles));
+    // four steps in flight (eight were measured too: 3-10 % slower, they halve the occupancy)
+    hipLaunchKernelGGL((linear_gemm_small_kernel<XDT, AXIS, 4>), grid, dim3(256), 0, stream,
+                       (const uint16_t*)X, (const uint16_t*)W_b, B_packed, v, Y, (int)M, (int)d_out,
+                       (int)d_in, y_dtype, m_tiles, n_tiles);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 template <int XDT, int AXIS, int BM, int WM>
 static int launch_gemm(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
                        void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
@@ -495,6 +655,12 @@ static int launch_gemm_bm(const void* X, const void* W_b, const uint32_t* B_pack
                           void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
                           hipStream_t stream)
 {
+    // Under-filled grids (at most 128 tiles of 256 x 128, i.e. a few hundred tokens): the
+    // small-tile kernel is 2-3x faster there; from about 1000 tokens on the big tiles win.
+    const int64_t big_tiles = ((M + 255) / 256) * ((d_out + kGemmBN - 1) / kGemmBN);
+    const int small = tune_value("gemm_small", -1);
+    if (d_in % 64 == 0 && (small == 1 || (small < 0 && big_tiles <= 128)))
+        return launch_gemm_small<XDT, AXIS>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
     if (M <= 128 || tune_value("gemm_bm", 256) == 128)
         return launch_gemm<XDT, AXIS, 128, 2>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
     // The pipelined kernel runs one workgroup per CU and is 10-18 % faster per tile; it pays off

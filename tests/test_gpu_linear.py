@@ -63,12 +63,14 @@ def test_decode_stack_shapes_batch1(shape, dtype):
 
 # prefill path: M > 64.  Ragged M, d_out and d_in around the 128 x 128 x 64 tile
 @pytest.mark.parametrize("M,d_out,d_in", [(65, 128, 64), (200, 100, 96), (256, 300, 160), (129, 257, 1024),
-                                          (128, 128, 32), (1000, 384, 512)])
+                                          (128, 128, 32), (1000, 384, 512), (70, 1000, 448), (300, 65, 192)])
 @pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
-@pytest.mark.parametrize("kernel", ["two_per_cu", "pipelined"])
+@pytest.mark.parametrize("kernel", ["two_per_cu", "pipelined", "small_tile"])
 def test_prefill_path_small_and_ragged(M, d_out, d_in, dtype, kernel, monkeypatch):
-    # both prefill kernels on every shape (the library would pick by tile count)
-    monkeypatch.setenv("PDELTA_TUNE", "gemm_pipe=1" if kernel == "pipelined" else "gemm_pipe=0")
+    # all three prefill kernels on every shape (the library would pick by tile count; the
+    # small-tile kernel needs d_in % 64 == 0 and otherwise leaves the shape to the others)
+    monkeypatch.setenv("PDELTA_TUNE", {"two_per_cu": "gemm_small=0,gemm_pipe=0", "pipelined": "gemm_small=0,gemm_pipe=1",
+                                       "small_tile": "gemm_small=1"}[kernel])
     L = make_case(d_out, d_in, M, dtype, "row", synth.seed_for(2, M + d_out + d_in))
     run_both_axes(L, (pd.F32, pd.F16 if dtype == synth.F16 else pd.BF16), f"prefill {M}x{d_out}x{d_in} dt={dtype}")
 
