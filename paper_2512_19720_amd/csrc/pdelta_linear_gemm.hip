@@ -68,6 +68,44 @@ __device__ __forceinline__ uint4v add_signed_scale(uint4v w, uint32_t negbits, u
     return r;
 }
 
+// Epilogue of the 64 x 64 wave tile for 16-bit outputs: the accumulators go through a wave-private
+// LDS region (32 rows x 64 columns at a time, rows padded to 144 bytes) and leave as 16-byte
+// stores, eight lanes per 128-byte line of Y.  Element-wise 2-byte stores of the MFMA layout cost
+// 1.7-1.9x the output bytes in HBM writes.  `region` holds 32 * kGemmLDK halves of this wave.
+// Returns false (nothing stored) when the tile is not fully inside Y or rows of Y are not
+// 16-byte aligned; the caller then stores element by element.
+template <int FM>
+__device__ __forceinline__ bool store_tile_16bit(const float16v (&acc)[FM][2], uint16_t* region, void* Y,
+                                                 int y_dtype, int tok0, int o0, int M, int d_out, int lane)
+{
+    if (y_dtype == kF32 || (d_out & 7) != 0 || o0 + 64 > d_out || tok0 + FM * 32 > M) return false;   // wave-uniform
+    uint16_t* Yh = (uint16_t*)Y;
+#pragma unroll
+    for (int f = 0; f < FM; ++f) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), col = h * 32 + (lane & 31);
+                const float val = acc[f][h][r];
+                region[row * kGemmLDK + col] =
+                    (uint16_t)(y_dtype == kBF16 ? f32_to_bf16_bits(val) : f32_to_f16_bits(val));
+            }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int row = it * 8 + (lane >> 3), chunk = lane & 7;
+            const uint4v vals = *(const uint4v*)(region + row * kGemmLDK + chunk * 8);
+            *(uint4v*)(Yh + (int64_t)(tok0 + f * 32 + row) * d_out + o0 + chunk * 8) = vals;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    return true;
+}
+
 // WM x 2 waves; a wave owns (BM / WM) tokens x 64 output rows.
 template <int XDT, int AXIS, int BM, int WM>
 __global__ void __launch_bounds__(WM * 128, (WM * 128) / 128)
@@ -229,9 +267,13 @@ linear_gemm_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ 
         store_lds();
         __syncthreads();
         multiply_stage();
+        __syncthreads();
     }
 
     // 32x32 accumulator: element r of lane l is row (r/4)*8 + (l/32)*4 + r%4, column l%32.
+    // (the loop ended with a barrier: the operand tiles in LDS are free)
+    if (store_tile_16bit<FM>(acc, Xs + wave * 32 * kGemmLDK, Y, y_dtype, m0 + wm * WROWS, n0 + wn * 64, M, d_out, lane))
+        return;
 #pragma unroll
     for (int f = 0; f < FM; ++f)
 #pragma unroll
@@ -436,6 +478,9 @@ linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restri
         __syncthreads();
     }
 
+    // (every step ended with a barrier: both LDS stages are free)
+    if (store_tile_16bit<FM>(acc, lds + wave * 32 * kGemmLDK, Y, y_dtype, m0 + wm * WROWS, n0 + wn * 64, M, d_out, lane))
+        return;
 #pragma unroll
     for (int f = 0; f < FM; ++f)
 #pragma unroll
