@@ -85,9 +85,8 @@ def test_pack_is_reproducible_and_ignores_workspace_contents():
 def test_pack_large_magnitudes_stay_exact():
     # |dW| up to ~1e5 and 4096 of them per row: sums near 2^28, still exact in both schemes
     rng = np.random.default_rng(2)
-    W_f = (rng.standard_normal((48, 4096)) * 3e4).astype(np.float16)
-    W_b = (rng.standard_normal((48, 4096)) * 3e4).astype(np.float16)
-    W_f, W_b = np.clip(W_f, -65000, 65000), np.clip(W_b, -65000, 65000)
+    W_f = np.clip(rng.standard_normal((48, 4096)) * 3e4, -65000, 65000).astype(np.float16)
+    W_b = np.clip(rng.standard_normal((48, 4096)) * 3e4, -65000, 65000).astype(np.float16)
     want = orc.pack(W_f, W_b)
     assert_pack_equal(gpu_pack(W_f.view(np.uint16), W_b.view(np.uint16), synth.F16), want, "large")
 
