@@ -318,6 +318,36 @@ def main() -> int:
                             "frac_hbm": round(stack_bytes / msg / 1e6 / HBM_PEAK_GBS, 4)}
         except Exception as exc:  # graph capture is an extra; the stream figure stands on its own
             res["graph"] = {"error": str(exc)[:200]}
+        # the same per-layer launches, but recorded on 8 forked streams so that the graph knows the
+        # layers are independent (they are here: each has its own X and Y) and may overlap them
+        try:
+            branches = [torch.cuda.Stream() for _ in range(8)]
+
+            def stack_pass_forked():
+                main = torch.cuda.current_stream()
+                for b in branches:
+                    b.wait_stream(main)
+                for li, ((d_out, d_in, axis, W_b, B, v), Y) in enumerate(zip(layers, Ys)):
+                    with torch.cuda.stream(branches[li % len(branches)]):
+                        if axis == "row":
+                            pd.pdelta_linear_row(Xs[d_in], W_b, B, v, out=Y)
+                        else:
+                            pd.pdelta_linear_col(Xs[d_in], W_b, B, v, out=Y)
+                for b in branches:
+                    main.wait_stream(b)
+
+            stack_pass_forked()
+            torch.cuda.synchronize()
+            gp = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gp):
+                stack_pass_forked()
+            timed(gp.replay, 2)
+            msp = timed(gp.replay, 10) / 10
+            res["graph_8_branches"] = {"ms_per_token": round(msp, 4), "tokens/s": round(1e3 / msp, 1),
+                                       "frac_hbm": round(stack_bytes / msp / 1e6 / HBM_PEAK_GBS, 4)}
+            del gp
+        except Exception as exc:
+            res["graph_8_branches"] = {"error": str(exc)[:200]}
         # the same 224 layers through the batched entry point: one launch instead of 224
         ROW_COL = {"row": pd.ROW, "col": pd.COL}
         plan = pd.pdelta_linear_batch_plan(
