@@ -9,3 +9,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def pytest_sessionstart(session):
+    """Load what is built; build only if nothing is (hipcc cross-compiles without a GPU)."""
+    lib = os.path.join(ROOT, "paper_2512_19720_amd", "libpdelta.so")
+    if not os.path.exists(lib):
+        from paper_2512_19720_amd import build as pdelta_build
+        pdelta_build.build_library()
