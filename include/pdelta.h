@@ -26,6 +26,9 @@
  *     kernel has been launched.  Inputs are never written.  Outputs must not alias inputs
  *     except where stated (pdelta_patch in place).
  *   - NaN / Inf inputs are outside the contract.
+ *   - Developer knob: the environment variable PDELTA_TUNE="key=value,..." overrides the library's
+ *     choice among its kernel variants (read at every call).  It changes no result beyond the
+ *     order of floating-point summation; without it the built-in choices apply.
  */
 #ifndef PDELTA_H
 #define PDELTA_H
