@@ -177,6 +177,22 @@ def main() -> int:
                 "bytes_per_launch": step_bytes // len(cases),
                 "avg_launch_us": round(avg_launch_us, 3), "traffic": traffic}
 
+    # what the box is, and what a plain streaming kernel reaches on it ("% of achievable")
+    props = torch.cuda.get_device_properties(0)
+    device_info = {"name": props.name, "arch": getattr(props, "gcnArchName", ""),
+                   "compute_units": props.multi_processor_count,
+                   "clock_MHz": round(getattr(props, "clock_rate", 0) / 1e3) if hasattr(props, "clock_rate") else None,
+                   "memory_GiB": round(props.total_memory / 2 ** 30, 1)}
+    csrc = torch.ones(1 << 29, dtype=f16, device=dev)                   # 1 GiB
+    cdst = torch.empty_like(csrc)
+    timed(lambda: torch.mul(csrc, 1.0, out=cdst), 3)
+    cms = timed(lambda: torch.mul(csrc, 1.0, out=cdst), 10) / 10
+    ceiling = {"kind": "torch elementwise copy of 1 GiB (1 GiB read + 1 GiB written)",
+               "GB/s": round(2 * (1 << 30) / cms / 1e6, 1),
+               "frac_hbm": round(2 * (1 << 30) / cms / 1e6 / HBM_PEAK_GBS, 4)}
+    del csrc, cdst
+    torch.cuda.empty_cache()
+
     out = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
@@ -187,6 +203,7 @@ def main() -> int:
                                "the K steps replayed from one HIP graph",
                    "bytes_per_step": step_bytes},
         "roofline": roofline, "decode_cases": per_case, "wall_s_timed_region": round(wall_s, 4),
+        "device": device_info, "achieved_ceiling": ceiling,
     }
     # ---------------- multi-variant decode: R requests share W_b, each has its own delta -------
     if "variants" not in skip:
