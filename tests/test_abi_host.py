@@ -336,3 +336,47 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(pd, "_LIB_PATH", "/nonexistent/libpdelta.so")
     with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
         pd.lib()
+
+
+def test_header_is_plain_c_and_struct_layouts_match_the_binding(tmp_path):
+    """include/pdelta.h must compile as C (it is the boundary), and the ctypes mirrors of its
+    structs must agree with the C compiler on size and field offsets."""
+    import subprocess
+    src = tmp_path / "layout.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "pdelta.h"
+int main(void) {
+    printf("pdelta_layer %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\n", sizeof(pdelta_layer),
+           offsetof(pdelta_layer, X), offsetof(pdelta_layer, W_b), offsetof(pdelta_layer, B_packed),
+           offsetof(pdelta_layer, v), offsetof(pdelta_layer, Y), offsetof(pdelta_layer, d_out),
+           offsetof(pdelta_layer, d_in), offsetof(pdelta_layer, axis), offsetof(pdelta_layer, first_block));
+    printf("pdelta_variant %zu %zu %zu\n", sizeof(pdelta_variant), offsetof(pdelta_variant, B_packed),
+           offsetof(pdelta_variant, v));
+    printf("pdelta_pack_job %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\n", sizeof(pdelta_pack_job),
+           offsetof(pdelta_pack_job, W_f), offsetof(pdelta_pack_job, W_b), offsetof(pdelta_pack_job, B_packed),
+           offsetof(pdelta_pack_job, v_row), offsetof(pdelta_pack_job, v_col), offsetof(pdelta_pack_job, workspace),
+           offsetof(pdelta_pack_job, workspace_bytes), offsetof(pdelta_pack_job, d_out), offsetof(pdelta_pack_job, d_in),
+           offsetof(pdelta_pack_job, first_tile), offsetof(pdelta_pack_job, first_fin_block),
+           offsetof(pdelta_pack_job, tile_blocks));
+    printf("enums %d %d %d %d %d %d\n", PDELTA_F16, PDELTA_BF16, PDELTA_F32, PDELTA_ROW, PDELTA_COL, PDELTA_EHIP);
+    return 0;
+}
+''')
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    lines = dict(l.split(" ", 1) for l in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                       text=True).stdout.strip().splitlines())
+
+    def layout(struct, fields):
+        return [ctypes.sizeof(struct)] + [getattr(struct, f).offset for f in fields]
+
+    assert list(map(int, lines["pdelta_layer"].split())) == layout(
+        pd.Layer, ["X", "W_b", "B_packed", "v", "Y", "d_out", "d_in", "axis", "first_block"])
+    assert list(map(int, lines["pdelta_variant"].split())) == layout(pd.Variant, ["B_packed", "v"])
+    assert list(map(int, lines["pdelta_pack_job"].split())) == layout(
+        pd.PackJob, ["W_f", "W_b", "B_packed", "v_row", "v_col", "workspace", "workspace_bytes", "d_out", "d_in",
+                     "first_tile", "first_fin_block", "tile_blocks"])
+    assert list(map(int, lines["enums"].split())) == [pd.F16, pd.BF16, pd.F32, pd.ROW, pd.COL, pd.EHIP]
