@@ -281,3 +281,43 @@ def test_patch_round_rounds_the_exact_sum_once():
             exact = Fraction(float(W_b[o, i])) + b * Fraction(float(v_c[i]))
             want = rne_f16_search(abs(exact)) | (0x8000 if exact < 0 else 0)
             assert int(got[o, i]) == want
+
+
+def test_swapping_the_models_flips_every_untied_sign_and_keeps_the_scales():
+    rng = np.random.default_rng(41)
+    W_f = h(rng.standard_normal((9, 96)) * 0.02)
+    W_b = h(rng.standard_normal((9, 96)) * 0.02)
+    W_f[:, :7] = W_b[:, :7]                                        # ties stay +1 both ways
+    B1, r1, c1 = orc.pack(W_f, W_b)
+    B2, r2, c2 = orc.pack(W_b, W_f)
+    U1, U2 = orc.unpack(B1, 96), orc.unpack(B2, 96)
+    tied = W_f.view(np.float16) == W_b.view(np.float16)
+    assert np.array_equal(U1[~tied], -U2[~tied]) and np.all(U1[tied] == 1.0) and np.all(U2[tied] == 1.0)
+    assert np.array_equal(r1, r2) and np.array_equal(c1, c2)       # |W_f - W_b| is symmetric
+
+
+def test_scaling_both_models_by_a_power_of_two_scales_the_scales_exactly():
+    rng = np.random.default_rng(42)
+    W_f = (rng.standard_normal((6, 64)) * 0.02).astype(np.float16)
+    W_b = (rng.standard_normal((6, 64)) * 0.02).astype(np.float16)
+    B1, r1, c1 = orc.pack(W_f.view(np.uint16), W_b.view(np.uint16))
+    B2, r2, c2 = orc.pack((W_f * np.float16(8)).view(np.uint16), (W_b * np.float16(8)).view(np.uint16))
+    assert np.array_equal(B1, B2)
+    assert np.array_equal(r2.view(np.float16), r1.view(np.float16) * np.float16(8))
+    assert np.array_equal(c2.view(np.float16), c1.view(np.float16) * np.float16(8))
+
+
+def test_rows_and_columns_are_independent():
+    # changing one entry changes its own word, its row scale and its column scale, nothing else
+    rng = np.random.default_rng(43)
+    W_f = h(rng.standard_normal((5, 64)) * 0.02)
+    W_b = h(rng.standard_normal((5, 64)) * 0.02)
+    B1, r1, c1 = orc.pack(W_f, W_b)
+    W_f2 = W_f.copy()
+    W_f2[3, 40] = h(np.array([W_b.view(np.float16)[3, 40] - np.float16(0.5)]))[0]
+    B2, r2, c2 = orc.pack(W_f2, W_b)
+    diff_words = np.argwhere(B1 != B2)
+    assert all(tuple(d) == (3, 1) for d in diff_words)             # entry (3, 40) lives in word [3][1]
+    assert (orc.unpack(B2, 64)[3, 40]) == -1.0
+    assert np.array_equal(np.delete(r1, 3), np.delete(r2, 3)) and r1[3] != r2[3]
+    assert np.array_equal(np.delete(c1, 40), np.delete(c2, 40)) and c1[40] != c2[40]
