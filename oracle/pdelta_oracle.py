@@ -37,7 +37,9 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        # PDELTA_ORACLE_LIB: used by the mutation test, which runs the pins against deliberately
+        # broken copies of the oracle to show that they notice
+        lib = ctypes.CDLL(os.environ.get("PDELTA_ORACLE_LIB") or build())
         i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
         lib.pdelta_ref_decode.restype = ctypes.c_double
         lib.pdelta_ref_decode.argtypes = [ctypes.c_uint16, i32]
