@@ -13,12 +13,14 @@
  *     to the host.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Work is enqueued on that stream and the call returns without synchronising; outputs are
  *     valid once the stream reaches that point.
- *   - The library allocates nothing and keeps no state between calls.
+ *   - The library allocates nothing and keeps no state between calls that affects a result
+ *     (it remembers, per device, that a kernel has been granted its dynamic-LDS size).
  *   - Matrices are dense row-major: W[o, i] at W + o*d_in + i, X[m, i] at X + m*d_in + i,
  *     Y[m, o] at Y + m*d_out + o.
  *   - Bit layout: entry (o, i) is bit (i % 32) of the uint32 B_packed[o * (d_in/32) + i/32];
- *     bit 1 means B = +1, bit 0 means B = -1 (consecutive input indices share a word, as the
- *     paper's "1 bit along the input axis").  sign(0) is +1: the bit is !(W_f < W_b).
+ *     bit 1 means B = +1, bit 0 means B = -1 (consecutive input indices share a word: the
+ *     masks are packed along the input axis, Implementation remarks).  sign(0) is +1: the bit
+ *     is !(W_f < W_b).
  *   - d_in must be a multiple of 32 (PDELTA_ESHAPE otherwise).  Every pointer must be 16-byte
  *     aligned (PDELTA_EALIGN).  v is always FP16 (Implementation remarks of the paper).
  *   - Return value: a pdelta_status.  All argument checks happen on the host before any HIP
@@ -27,7 +29,7 @@
  *     except where stated (pdelta_patch in place).
  *   - NaN / Inf inputs are outside the contract.
  *   - Developer knob: the environment variable PDELTA_TUNE="key=value,..." overrides the library's
- *     choice among its kernel variants (read at every call).  It changes no result beyond the
+ *     choice among its kernel variants (read once per call).  It changes no result beyond the
  *     order of floating-point summation; without it the built-in choices apply.
  */
 #ifndef PDELTA_H
@@ -71,7 +73,7 @@ size_t pdelta_pack_workspace_bytes(int64_t d_out, int64_t d_in);
  * Offline companion: sign + bit-pack + per-axis scale initialisation.
  *   B      = sign(W_f - W_b)                            (Section 2, definition of B)
  *   Pack   : one bit per entry along the input axis     (per-layer compression algorithm,
- *                                                        step "B <- Pack(sign(dW)^T)")
+ *                                                        packing step)
  *   v_row[o] = mean_i |W_f[o,i] - W_b[o,i]|,  v_col[i] = mean_o |W_f[o,i] - W_b[o,i]|
  *            (same algorithm, initial values of the Row and Col scale vectors), each the
  *            exact mean rounded once to FP16 (nearest-even).
@@ -107,6 +109,20 @@ int pdelta_pack(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, i
  * Products of the 16-bit operands are accumulated in fp32; Y is rounded to y_dtype once
  * (nearest-even).  M = 0 is a no-op that returns PDELTA_OK (X and Y may then be NULL).  No
  * bias term (the paper leaves biases untouched, Limitations section).
+ * Arithmetic and operand range, by batch size:
+ *   M <= 64  the matrix cores multiply in the operands' own format (fp16 or bf16) with one
+ *            accumulator for X W_b^T and one for X B^T; v_row multiplies the latter in fp32.
+ *            Every finite input is in range.
+ *   M > 64   one multiplication stream in fp16: the tile of W_hat = W_b +- v_row is formed as
+ *            fp16(W_b + v B) with one rounding (relative error <= 2^-11 per weight, about 2e-4
+ *            relative on Y for LLM-like weights), so a delta smaller than half an fp16 ulp of
+ *            W_b (|v| < 2^-12 |W_b|) is partly rounded away.  bf16 X and W_b are converted to
+ *            fp16 on the way, truncating toward zero: exact for magnitudes in [2^-14, 65504];
+ *            smaller magnitudes lose their low bits (absolute error < 2^-24); magnitudes above
+ *            65504 are OUTSIDE the contract for bf16 at M > 64 (they would become the largest
+ *            fp16 value).  fp16 inputs are used as they are.
+ * The results of both regimes satisfy the same tolerance against exact arithmetic
+ * (max |err| <= 1e-2 RMS(Y), relative Frobenius error <= 1e-3) on inputs inside these ranges.
  */
 int pdelta_linear_row(const void* X, const void* W_b, const uint32_t* B_packed,
                       const uint16_t* v_row, void* Y, int64_t M, int64_t d_out, int64_t d_in,
@@ -115,7 +131,10 @@ int pdelta_linear_row(const void* X, const void* W_b, const uint32_t* B_packed,
 /*
  * Delta linear layer, column mode (Eq. 1 with v in R^(d_in x 1)):
  *   Y[m,o] = sum_i X[m,i] * W_b[o,i]  +  sum_i (X[m,i] * v_col[i]) * B[o,i]
- * Arguments as pdelta_linear_row, with v_col FP16 [d_in].
+ * Arguments as pdelta_linear_row, with v_col FP16 [d_in].  Arithmetic as there, except that for
+ * M <= 64 the sign part's operand is fp16(X[m,i] * v_col[i]) (one extra rounding of relative size
+ * 2^-11 on the delta term; for bf16 X the product must stay below 65504 in magnitude), and for
+ * M > 64 v_col[i] enters the fp16 tile of W_hat column by column.
  */
 int pdelta_linear_col(const void* X, const void* W_b, const uint32_t* B_packed,
                       const uint16_t* v_col, void* Y, int64_t M, int64_t d_out, int64_t d_in,
@@ -226,8 +245,9 @@ int pdelta_pack_batch(const pdelta_pack_job* jobs_host, const pdelta_pack_job* j
  * computes for M = 1 with (B_r, v_r) (Eq. 1 inside the layer forward):
  *   row:  Y[r,o] = sum_i X[r,i] W_b[o,i] + v_r[o] * sum_i X[r,i] B_r[o,i]
  *   col:  Y[r,o] = sum_i X[r,i] W_b[o,i] +          sum_i (X[r,i] v_r[i]) B_r[o,i]
- * but W_b is read once for all requests (2 + R/8 bytes per weight) when R <= 16 and d_in is a
- * multiple of 128; otherwise the requests run one after the other with the same results.
+ * but W_b is read once per group of up to 16 requests (2 + R/8 bytes per weight for R <= 16)
+ * when d_in is a multiple of 128; otherwise the requests run one after the other with the
+ * same results.
  * Arguments
  *   X         in   [R, d_in], dtype x_dtype; row r is the token of request r
  *   W_b       in   [d_out, d_in], same dtype

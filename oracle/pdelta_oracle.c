@@ -13,7 +13,7 @@
  *   v_0     = mean |Delta W| taken per output row / per input column        (Alg. "Per-layer
  *             compression with Row/Col selection", initialisation of v_r and v_c)
  *   Pack    = one bit per entry, consecutive input indices share a word     (Implementation
- *             remarks: masks stay packed, 1 bit along the input axis)
+ *             remarks: the masks are kept bit-packed along the input axis)
  *
  * Everything floating point is done in fp64 on values decoded exactly from their 16-bit
  * storage format.  Nothing is blocked, fused or reordered: W_hat is rebuilt densely and the
@@ -188,7 +188,7 @@ int pdelta_patch_ref(const uint16_t* W_b, const uint32_t* B_packed, const uint16
 }
 
 /* The merged weights as they would be stored: one RNE rounding of the exact fp64 sum to the
- * weight dtype ("add all residual terms at once", Limitations section).                      */
+ * weight dtype (the one-time merge of every residual term, Limitations section).             */
 int pdelta_patch_round_ref(const uint16_t* W_b, const uint32_t* B_packed, const uint16_t* v,
                            int axis, int64_t d_out, int64_t d_in, int w_dtype, uint16_t* W_out)
 {
@@ -257,7 +257,6 @@ int pdelta_linear_ref_at(const uint16_t* X, const uint16_t* W_b, const uint32_t*
     return REF_OK;
 }
 
-/* Number of threads the parallel loops above will use (for the bench's "cores" field). */
 /*
  * Gradient of a loss with respect to the scale vector, given dY = dL/dY (algorithm "Train
  * per-row/column scaling vectors via activation matching": the loss is backpropagated through
@@ -298,6 +297,7 @@ int pdelta_grad_v_ref(const uint16_t* X, const uint16_t* dY, const uint32_t* B_p
     return 0;
 }
 
+/* Number of threads the parallel loops above will use (for the bench's "cores" field). */
 int pdelta_ref_threads(void)
 {
 #ifdef _OPENMP

@@ -34,12 +34,24 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def use_library(path: str) -> None:
+    """Load the oracle from `path` instead of building pdelta_oracle.c.  Only the mutation test
+    calls this (through the pytest option --oracle-lib of its child run): it points the pins at
+    deliberately broken copies of the oracle to show that they notice.  Must come before the
+    first call into the oracle."""
+    global _lib_override
+    if _lib is not None:
+        raise RuntimeError("the oracle library is already loaded")
+    _lib_override = path
+
+
+_lib_override = None
+
+
 def _load():
     global _lib
     if _lib is None:
-        # PDELTA_ORACLE_LIB: used by the mutation test, which runs the pins against deliberately
-        # broken copies of the oracle to show that they notice
-        lib = ctypes.CDLL(os.environ.get("PDELTA_ORACLE_LIB") or build())
+        lib = ctypes.CDLL(_lib_override or build())
         i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
         lib.pdelta_ref_decode.restype = ctypes.c_double
         lib.pdelta_ref_decode.argtypes = [ctypes.c_uint16, i32]

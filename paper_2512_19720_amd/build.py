@@ -18,7 +18,6 @@ SOURCES = ["pdelta_api.hip", "pdelta_pack.hip", "pdelta_patch.hip", "pdelta_line
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",     # no packed-fp32 codegen
-    "-munsafe-fp-atomics",                                            # hardware fp64 atomic add
     "-Wall", "-Wno-unused-function",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]

@@ -9,9 +9,26 @@
 
 namespace pdelta {
 
+// PDELTA_TUNE is looked up in the environment once per C-ABI call (TuneScope, opened by every
+// entry point that launches); inside the call the kernel selectors read the snapshot.  Without
+// the variable a lookup costs one thread-local load.
+namespace {
+thread_local const char* t_tune_env = nullptr;
+thread_local int t_tune_depth = 0;
+}  // namespace
+
+TuneScope::TuneScope()
+{
+    if (t_tune_depth++ == 0) t_tune_env = getenv("PDELTA_TUNE");
+}
+TuneScope::~TuneScope()
+{
+    if (--t_tune_depth == 0) t_tune_env = nullptr;
+}
+
 int tune_value(const char* key, int fallback)
 {
-    const char* env = getenv("PDELTA_TUNE");
+    const char* env = t_tune_depth > 0 ? t_tune_env : getenv("PDELTA_TUNE");
     if (env == nullptr) return fallback;
     const size_t klen = strlen(key);
     for (const char* p = env; *p != '\0';) {
@@ -21,6 +38,17 @@ int tune_value(const char* key, int fallback)
         p = comma + 1;
     }
     return fallback;
+}
+
+int opt_in_dynamic_lds(const void* kernel, int bytes, unsigned* done_mask)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return -1;
+    const unsigned bit = 1u << (dev & 31);
+    if (__atomic_load_n(done_mask, __ATOMIC_ACQUIRE) & bit) return 0;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return -1;
+    __atomic_fetch_or(done_mask, bit, __ATOMIC_RELEASE);
+    return 0;
 }
 
 namespace {
@@ -55,6 +83,7 @@ int linear_common(const void* X, const void* W_b, const uint32_t* B_packed, cons
                   void* Y, int64_t M, int64_t d_out, int64_t d_in, int x_dtype, int y_dtype,
                   int axis, void* stream)
 {
+    const TuneScope tune_scope;
     if (const int rc = linear_check(X, W_b, B_packed, v, Y, M, d_out, d_in, x_dtype, y_dtype, axis))
         return rc;
     if (M == 0) return PDELTA_OK;
@@ -115,9 +144,21 @@ static int pack_check(const void* W_f, const void* W_b, int64_t d_out, int64_t d
     if (misaligned(W_f) || misaligned(W_b) || misaligned(B_packed) || misaligned(v_row) ||
         misaligned(v_col) || (want_scales && misaligned(workspace)))
         return PDELTA_EALIGN;
+    // no output (signs, scale vectors, scratch) may share a byte with an input or another output
     const size_t w_bytes = (size_t)d_out * d_in * 2, b_bytes = (size_t)d_out * d_in / 8;
-    if (overlaps(B_packed, b_bytes, W_f, w_bytes) || overlaps(B_packed, b_bytes, W_b, w_bytes))
-        return PDELTA_EINVAL;
+    struct Range { const void* p; size_t n; };
+    const Range in[2] = {{W_f, w_bytes}, {W_b, w_bytes}};
+    const Range out[4] = {{B_packed, b_bytes},
+                          {v_row, v_row ? (size_t)d_out * 2 : 0},
+                          {v_col, v_col ? (size_t)d_in * 2 : 0},
+                          {want_scales ? workspace : nullptr, want_scales ? workspace_bytes : 0}};
+    for (int a = 0; a < 4; ++a) {
+        if (out[a].n == 0) continue;
+        for (int b = 0; b < 2; ++b)
+            if (overlaps(out[a].p, out[a].n, in[b].p, in[b].n)) return PDELTA_EINVAL;
+        for (int b = a + 1; b < 4; ++b)
+            if (out[b].n != 0 && overlaps(out[a].p, out[a].n, out[b].p, out[b].n)) return PDELTA_EINVAL;
+    }
     return PDELTA_OK;
 }
 
@@ -126,6 +167,7 @@ int pdelta_pack(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, i
                 size_t workspace_bytes, void* stream)
 {
     using namespace pdelta;
+    const TuneScope tune_scope;
     if (const int rc = pack_check(W_f, W_b, d_out, d_in, w_dtype, B_packed, v_row, v_col, workspace,
                                   workspace_bytes))
         return rc;
@@ -158,6 +200,7 @@ int pdelta_pack_batch(const pdelta_pack_job* jobs_host, const pdelta_pack_job* j
                       int32_t n_jobs, int w_dtype, void* stream)
 {
     using namespace pdelta;
+    const TuneScope tune_scope;
     if (n_jobs < 0) return PDELTA_EINVAL;
     if (n_jobs == 0) return PDELTA_OK;
     if (jobs_host == nullptr || jobs_device == nullptr) return PDELTA_EINVAL;
@@ -216,6 +259,7 @@ int pdelta_patch(const void* W_b, const uint32_t* B_packed, const uint16_t* v, i
                  void* W_out, int64_t d_out, int64_t d_in, int w_dtype, void* stream)
 {
     using namespace pdelta;
+    const TuneScope tune_scope;
     if (const int rc = patch_check(W_b, B_packed, v, axis, W_out, d_out, d_in, w_dtype)) return rc;
     const int rc = launch_patch_dispatch(w_dtype, axis, W_b, B_packed, v, W_out, d_out, d_in,
                                          (hipStream_t)stream);
@@ -226,6 +270,7 @@ int pdelta_patch_batch(const pdelta_layer* layers_host, const pdelta_layer* laye
                        int32_t n_layers, int w_dtype, void* stream)
 {
     using namespace pdelta;
+    const TuneScope tune_scope;
     if (n_layers < 0) return PDELTA_EINVAL;
     if (n_layers == 0) return PDELTA_OK;
     if (layers_host == nullptr || layers_device == nullptr) return PDELTA_EINVAL;
@@ -261,6 +306,7 @@ int pdelta_linear_batch(const pdelta_layer* layers_host, const pdelta_layer* lay
                         int32_t n_layers, int64_t M, int x_dtype, int y_dtype, void* stream)
 {
     using namespace pdelta;
+    const TuneScope tune_scope;
     if (n_layers < 0 || M < 0) return PDELTA_EINVAL;
     if (n_layers == 0) return PDELTA_OK;
     if (layers_host == nullptr || layers_device == nullptr) return PDELTA_EINVAL;
@@ -297,6 +343,7 @@ int pdelta_linear_variants(const void* X, const void* W_b, const pdelta_variant*
                            int64_t d_out, int64_t d_in, int x_dtype, int y_dtype, void* stream)
 {
     using namespace pdelta;
+    const TuneScope tune_scope;
     if (R < 0) return PDELTA_EINVAL;
     if (R > 0 && (variants_host == nullptr || variants_device == nullptr)) return PDELTA_EINVAL;
     if (misaligned(variants_device)) return PDELTA_EALIGN;
@@ -334,6 +381,7 @@ int pdelta_grad_v(const void* X, const void* dY, const uint32_t* B_packed, int a
                   size_t workspace_bytes, void* stream)
 {
     using namespace pdelta;
+    const TuneScope tune_scope;
     if (B_packed == nullptr || grad_v == nullptr) return PDELTA_EINVAL;
     if (axis != PDELTA_ROW && axis != PDELTA_COL) return PDELTA_EINVAL;
     if (M < 0) return PDELTA_EINVAL;

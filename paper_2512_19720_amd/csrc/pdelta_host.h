@@ -42,8 +42,8 @@ int launch_linear_skinny_batch(int x_dtype, int y_dtype, const ::pdelta_layer* l
                                const ::pdelta_layer* layers_device, int n_layers, int64_t M,
                                hipStream_t stream);
 
-// R requests (one token each) that share W_b and each have their own delta.  Returns 1 when the
-// fused kernel does not apply (R > 16 or d_in % 128 != 0), else 0 / -1.
+// R requests (one token each) that share W_b and each have their own delta (more than 16 requests
+// run in chunks of 16).  Returns 1 when the fused kernel does not apply (d_in % 128 != 0), else 0 / -1.
 int launch_linear_variants(int x_dtype, int y_dtype, int axis, const void* X, const void* W_b,
                            const ::pdelta_variant* variants_device, int R, void* Y, int64_t d_out,
                            int64_t d_in, hipStream_t stream);
@@ -59,8 +59,20 @@ int launch_linear_gemm(int x_dtype, int y_dtype, int axis, const void* X, const 
                        const uint32_t* B_packed, const uint16_t* v, void* Y, int64_t M,
                        int64_t d_out, int64_t d_in, hipStream_t stream);
 
-// Integer tuning knobs read once from the environment variable PDELTA_TUNE
-// ("key=value,key=value"); returns `fallback` when the key is absent.
+// Integer tuning knobs from the environment variable PDELTA_TUNE ("key=value,key=value");
+// returns `fallback` when the key is absent.  Every C-ABI entry point that launches opens a
+// TuneScope, which reads the variable once for the whole call.
+struct TuneScope {
+    TuneScope();
+    ~TuneScope();
+    TuneScope(const TuneScope&) = delete;
+    TuneScope& operator=(const TuneScope&) = delete;
+};
 int tune_value(const char* key, int fallback);
+
+// Kernels that use more dynamic LDS than the default limit have to opt in once per device.
+// `done_mask` is a static word of the call site (one bit per device): the attribute is set on
+// the first launch on a device and never again.  Returns 0, or -1 when the runtime refuses.
+int opt_in_dynamic_lds(const void* kernel, int bytes, unsigned* done_mask);
 
 }  // namespace pdelta

@@ -512,9 +512,8 @@ static int launch_gemm_pipe(const void* X, const void* W_b, const uint32_t* B_pa
     const int n_groups = (n_tiles + kXcds - 1) / kXcds;
     const dim3 grid((unsigned)((int64_t)n_groups * kXcds * m_tiles));
     auto kernel = linear_gemm_pipe_kernel<XDT, AXIS>;
-    if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
-        hipSuccess)
-        return -1;
+    static unsigned lds_opted_in = 0;                 // per template instance: one kernel
+    if (opt_in_dynamic_lds((const void*)kernel, (int)lds, &lds_opted_in) != 0) return -1;
     hipLaunchKernelGGL(kernel, grid, dim3(512), lds, stream, (const uint16_t*)X, (const uint16_t*)W_b,
                        B_packed, v, Y, (int)M, (int)d_out, (int)d_in, y_dtype, m_tiles, n_tiles);
     return hipGetLastError() == hipSuccess ? 0 : -1;

@@ -481,11 +481,9 @@ static int launch_staged(const void* X, const void* W_b, const uint32_t* B_packe
 {
     const dim3 grid((unsigned)((d_out + 15) / 16));
     auto kernel = linear_skinny_staged_kernel<XDT, AXIS, WAVES, DEPTH, STAGE_X>;
-    if (lds > 48 * 1024) {   // above the default dynamic-LDS limit the kernel has to opt in
-        if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)kStagedLdsLimit) != hipSuccess)
-            return -1;
-    }
+    static unsigned lds_opted_in = 0;                 // per template instance: one kernel
+    if (lds > 48 * 1024 && opt_in_dynamic_lds((const void*)kernel, (int)kStagedLdsLimit, &lds_opted_in) != 0)
+        return -1;           // above the default dynamic-LDS limit the kernel has to opt in (once)
     hipLaunchKernelGGL(kernel, grid, dim3(WAVES * 64), lds, stream, (const uint16_t*)X,
                        (const uint16_t*)W_b, B_packed, v, Y, (int)M, (int)d_out, (int)d_in, y_dtype);
     return hipGetLastError() == hipSuccess ? 0 : -1;
@@ -597,10 +595,9 @@ int launch_linear_skinny_batch(int x_dtype, int y_dtype, const pdelta_layer* lay
     void (*kernel)(const pdelta_layer*, int, int, int);
     if (x_dtype == kBF16) kernel = stage_x ? linear_skinny_batch_kernel<kBF16, 8, 2, true> : linear_skinny_batch_kernel<kBF16, 8, 2, false>;
     else kernel = stage_x ? linear_skinny_batch_kernel<kF16, 8, 2, true> : linear_skinny_batch_kernel<kF16, 8, 2, false>;
-    if (lds > 48 * 1024 &&
-        hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)kStagedLdsLimit) != hipSuccess)
-        return -1;
+    static unsigned lds_opted_in[4] = {0, 0, 0, 0};   // one word per kernel chosen above
+    unsigned* done = &lds_opted_in[(x_dtype == kBF16 ? 2 : 0) + (stage_x ? 1 : 0)];
+    if (lds > 48 * 1024 && opt_in_dynamic_lds((const void*)kernel, (int)kStagedLdsLimit, done) != 0) return -1;
     hipLaunchKernelGGL(kernel, dim3((unsigned)total), dim3(8 * 64), lds, stream, layers_device,
                        n_layers, (int)M, y_dtype);
     return hipGetLastError() == hipSuccess ? 0 : -1;

@@ -253,8 +253,8 @@ static int launch_variants_one(const void* X, const void* W_b, const pdelta_vari
 {
     const size_t lds = STAGE ? (size_t)R * 16 * (d_in / 8 + 16) : 0;
     auto kernel = linear_variants_kernel<XDT, AXIS, NQ, STAGE>;
-    if (lds > 32 * 1024 && hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               (int)kVarStageBytes) != hipSuccess)
+    static unsigned lds_opted_in = 0;                 // per template instance: one kernel
+    if (lds > 32 * 1024 && opt_in_dynamic_lds((const void*)kernel, (int)kVarStageBytes, &lds_opted_in) != 0)
         return -1;
     hipLaunchKernelGGL(kernel, dim3((unsigned)((d_out + 15) / 16)), dim3(512), lds, stream, (const uint16_t*)X,
                        (const uint16_t*)W_b, variants_device, R, Y, (int)d_out, (int)d_in, y_dtype);

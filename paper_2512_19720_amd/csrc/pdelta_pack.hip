@@ -1,6 +1,6 @@
 // pdelta_pack: B = sign(W_f - W_b) bit-packed along the input axis, plus the per-axis
 // mean |W_f - W_b| that initialises the scale vectors (paper Section 2; per-layer compression
-// algorithm: "B <- Pack(sign(dW)^T)", "v_c <- mean(|dW|, axis=1)", "v_r <- mean(|dW|, axis=0)").
+// algorithm: the packing step and the initial values of the Row and Col scale vectors).
 //
 // One streaming pass over both matrices (4 B read, 1/8 B written per weight): HBM-bound.
 //   pack_main_kernel      signs -> words; |dW| -> one partial sum per (row, column tile) and

@@ -1,6 +1,6 @@
-// pdelta_patch: W_out = round(W_b + v (.) B)  (paper Eq. 1), the merge the paper deploys with
-// ("add all residual terms at once", Limitations; "Model-wide application from a saved delta
-// file").  Streaming, HBM-bound: 2 + 1/8 bytes read and 2 bytes written per weight.
+// pdelta_patch: W_out = round(W_b + v (.) B)  (paper Eq. 1): the one-time merge of the delta into
+// the weights that the paper deploys with (Limitations section; algorithm for applying a saved
+// delta file model-wide).  Streaming, HBM-bound: 2 + 1/8 bytes read and 2 bytes written per weight.
 //
 // Rounding.  The result is the exact sum of two 16-bit floats rounded ONCE to the weight dtype
 // (nearest-even).  The sum is formed twice in fp32, rounded down and rounded up (the fp32

@@ -7,8 +7,18 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+def pytest_addoption(parser):
+    parser.addoption("--oracle-lib", default=None,
+                     help="run the oracle pins against this shared library instead of the built oracle "
+                          "(used only by tests/test_oracle_mutations.py for its child runs)")
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    path = config.getoption("--oracle-lib")
+    if path:
+        from oracle import pdelta_oracle
+        pdelta_oracle.use_library(path)
 
 
 def pytest_sessionstart(session):

@@ -305,6 +305,15 @@ def test_pack_argument_errors():
     assert call_pack(Wf=A + 2) == pd.EALIGN
     assert call_pack(vr=A + 0x3000000 + 2) == pd.EALIGN
     assert call_pack(B=A + 32) == pd.EINVAL                             # B_packed inside W_f
+    # every output and the scratch must be disjoint from the inputs and from each other
+    assert call_pack(vr=A + 64) == pd.EINVAL                            # v_row inside W_f
+    assert call_pack(vc=A + 0x1000000 + 64) == pd.EINVAL                # v_col inside W_b
+    assert call_pack(ws=A) == pd.EINVAL                                 # workspace on top of W_f
+    assert call_pack(ws=A + 0x1000000, wsb=1 << 12) == pd.EINVAL        # workspace on top of W_b
+    assert call_pack(vr=A + 0x2000000) == pd.EINVAL                     # v_row on top of B_packed
+    assert call_pack(vc=A + 0x3000000 + 64) == pd.EINVAL                # v_col inside v_row
+    assert call_pack(ws=A + 0x3100000 - 4096) == pd.EINVAL              # workspace reaches into v_col
+    assert call_pack(ws=A + 0x2000000) == pd.EINVAL                     # workspace on top of B_packed
 
 
 def call_patch(W=A, B=A + 0x1000000, v=A + 0x2000000, axis=pd.ROW, out=A + 0x3000000, d_out=64,

@@ -45,9 +45,8 @@ def test_pins_catch_the_planted_mistake(name, old, new, files, tmp_path):
     mutant_so = tmp_path / "libmutant.so"
     subprocess.run(["gcc", "-O1", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off", "-o", str(mutant_so),
                     str(mutant_c), "-lm"], check=True)
-    env = dict(os.environ, PDELTA_ORACLE_LIB=str(mutant_so))
     res = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
-                          *[os.path.join(ROOT, "tests", f) for f in files]],
-                         cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
+                          "--oracle-lib", str(mutant_so), *[os.path.join(ROOT, "tests", f) for f in files]],
+                         cwd=ROOT, capture_output=True, text=True, timeout=600)
     assert res.returncode != 0, f"no pin noticed: {name}\n{res.stdout[-2000:]}"
     assert " failed" in res.stdout or " error" in res.stdout, res.stdout[-2000:]
