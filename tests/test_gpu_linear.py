@@ -127,6 +127,82 @@ def test_config2_prefill_full_size_sampled_outputs(shape, kernel, monkeypatch):
         check_y(got, ref.reshape(1, -1), f"config2 {shape} y={yd}")
 
 
+_WHOLE_ROW_REF = {}
+
+
+def whole_row_reference(shape):
+    """Config 2 at full size, oracle side: 64 whole rows of Y (all d_out outputs each), spread
+    over all eight 256-token tiles at different offsets inside the tile, so that every
+    (token tile, output tile) cell of the launch is compared.  Computed once per shape."""
+    if shape not in _WHOLE_ROW_REF:
+        d_out, d_in = shape
+        M = 2048
+        seed = synth.seed_for(2, d_out % 1000 + d_in % 1000)
+        Ld = synth.layer_device(d_out, d_in, synth.BF16, "row", seed, DEV)
+        X = synth.x_device(M, d_in, synth.BF16, seed + 1, DEV)
+        rng = np.random.default_rng(seed + 2)
+        m_rows = np.unique(np.concatenate([[0, M - 1], (np.arange(62) % 8) * 256 + rng.integers(0, 256, 62)]))
+        Wb, dW = synth.torch_to_bits(Ld["W_b"]), synth.torch_to_bits(Ld["dW"])
+        Bo, vo, _ = orc.pack(dW, np.zeros_like(dW), orc.BF16, want_col=False)
+        Xh = synth.torch_to_bits(X[torch.from_numpy(m_rows).to(DEV)])
+        ref = orc.linear(Xh, Wb, Bo, vo, orc.ROW, orc.BF16)
+        _WHOLE_ROW_REF[shape] = (seed, m_rows, Bo, vo, ref)
+    return _WHOLE_ROW_REF[shape]
+
+
+@pytest.mark.parametrize("shape", synth.PREFILL_SHAPES)
+@pytest.mark.parametrize("kernel", ["default", "pipelined"])
+def test_config2_prefill_full_size_whole_rows(shape, kernel, monkeypatch):
+    """bf16, M = 2048, the benchmark's launch configuration: at least 64 whole rows of Y against
+    the fp64 oracle, fp32 output under the stated bounds and bf16 output under the bounds widened
+    by the final rounding; the packed signs and scales the GPU used are the oracle's, bit for bit."""
+    if kernel == "pipelined":
+        monkeypatch.setenv("PDELTA_TUNE", "gemm_pipe=1")
+    seed, m_rows, Bo, vo, ref = whole_row_reference(shape)
+    d_out, d_in = shape
+    Ld = synth.layer_device(d_out, d_in, synth.BF16, "row", seed, DEV)
+    X = synth.x_device(2048, d_in, synth.BF16, seed + 1, DEV)
+    B, v_row, _ = pd.pdelta_pack(Ld["dW"], torch.zeros_like(Ld["dW"]))
+    torch.cuda.synchronize()
+    assert np.array_equal(words_host(B), Bo) and np.array_equal(synth.torch_to_bits(v_row), vo)
+    assert len(m_rows) >= 60
+    rows_t = torch.from_numpy(m_rows).to(DEV)
+    for yd in (torch.float32, torch.bfloat16):
+        Y = gpu_linear(orc.ROW, X, Ld["W_b"], B, v_row, yd)
+        check_y(Y[rows_t], ref, f"config2 whole rows {shape} kernel={kernel} y={yd}")
+
+
+def spread_bits(rng, shape, lo_exp, hi_exp, dtype):
+    """Random signs, magnitudes log-uniform over [2^lo_exp, 2^hi_exp), as storage bit patterns."""
+    mag = np.exp2(rng.uniform(lo_exp, hi_exp, shape))
+    return synth.to_storage_bits((mag * rng.choice([-1.0, 1.0], shape)).astype(np.float32), dtype)
+
+
+@pytest.mark.parametrize("M", [64, 65, 300])
+@pytest.mark.parametrize("tiny", [False, True])
+def test_bf16_operand_range_of_both_batch_regimes(M, tiny):
+    """bf16 operands over the whole range the header states for M > 64 (magnitudes from 2^-14 up
+    to 6e4), and with a sprinkling of values just below 2^-14 (`tiny`), at the last batch size of
+    the decode regime (64) and in the prefill regime (65, 300): every case meets the stated
+    tolerance against the fp64 oracle, so the meaning of the call does not change with M inside
+    the documented range."""
+    rng = np.random.default_rng(700 + M + (1 if tiny else 0))
+    d_out, d_in = 192, 512
+    X = spread_bits(rng, (M, d_in), -14.0, np.log2(6.0e4), synth.BF16)
+    W_b = spread_bits(rng, (d_out, d_in), -14.0, np.log2(6.0e4), synth.BF16)
+    if tiny:
+        for A in (X, W_b):
+            mask = rng.random(A.shape) < 0.05
+            A[mask] = spread_bits(rng, A.shape, -16.0, -14.0, synth.BF16)[mask]
+    dW = spread_bits(rng, (d_out, d_in), -12.0, -4.0, synth.BF16)      # v <= 2^-4: fp16(X v_col) stays finite
+    Bo, v_row, v_col = orc.pack(dW, np.zeros_like(dW), orc.BF16)
+    Xd, Wd, Bd = to_dev(X, synth.BF16), to_dev(W_b, synth.BF16), words_dev(Bo)
+    for axis, v in ((orc.ROW, v_row), (orc.COL, v_col)):
+        ref = orc.linear(X, W_b, Bo, v, axis, orc.BF16)
+        Y = gpu_linear(axis, Xd, Wd, Bd, f16_dev(v), torch.float32)
+        check_y(Y, ref, f"operand range M={M} tiny={tiny} axis={axis}")
+
+
 @pytest.mark.parametrize("d_out,d_in,M", [(8192, 28672, 4), (50304, 4096, 16), (8192, 28672, 300)])
 def test_very_large_layers_sampled(d_out, d_in, M):
     """Shapes of a 70B-class MLP and of a vocabulary head (up to 470 MB of weights): pack, both
