@@ -97,6 +97,25 @@ int pdelta_pack(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, i
                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * pdelta_pack for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and error codes as pdelta_pack, minus the workspace: the partial sums go to an array
+ * of pdelta_pack_noalloc_max_bytes() bytes (16 MiB) that the library owns, one copy per GPU,
+ * resident until the process ends.  The call allocates and frees nothing.
+ *   - Layers whose pdelta_pack_workspace_bytes(d_out, d_in) exceeds that size are rejected with
+ *     PDELTA_EWORKSPACE when a scale vector is asked for (with v_row = v_col = NULL any size
+ *     is accepted: the signs need no scratch).  16 MiB covers every projection of 7B / 8B-class
+ *     models (14336 x 4096 needs 7.5 MiB).
+ *   - All calls on one GPU share that GPU's array: two calls that may run at the same time on
+ *     one GPU (different streams, different threads) race on it and give wrong scales.  Calls on
+ *     one stream are ordered and safe; the contents left by one call are never read by the next.
+ *   - PDELTA_EHIP when the runtime cannot give the array's device address.
+ */
+size_t pdelta_pack_noalloc_max_bytes(void);
+int pdelta_pack_noalloc(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, int w_dtype,
+                        uint32_t* B_packed, uint16_t* v_row, uint16_t* v_col, void* stream);
+
+/*
  * Delta linear layer, row mode (Eq. 1 with v in R^(1 x d_out), then the layer forward
  * Y = X W_hat^T), evaluated without forming W_hat in memory:
  *   Y[m,o] = sum_i X[m,i] * W_b[o,i]  +  v_row[o] * sum_i X[m,i] * B[o,i]

@@ -61,6 +61,10 @@ def lib() -> ctypes.CDLL:
         L.pdelta_pack_workspace_bytes.argtypes = [i64, i64]
         L.pdelta_pack.restype = i32
         L.pdelta_pack.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp, sz, vp]
+        L.pdelta_pack_noalloc_max_bytes.restype = sz
+        L.pdelta_pack_noalloc_max_bytes.argtypes = []
+        L.pdelta_pack_noalloc.restype = i32
+        L.pdelta_pack_noalloc.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp]
         for name in ("pdelta_linear_row", "pdelta_linear_col"):
             f = getattr(L, name)
             f.restype = i32
@@ -149,6 +153,21 @@ def pdelta_pack(W_f: torch.Tensor, W_b: torch.Tensor, want_row: bool = True, wan
                            _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                            _stream())
     _check(rc, "pdelta_pack")
+    return B, v_row, v_col
+
+
+def pdelta_pack_noalloc(W_f: torch.Tensor, W_b: torch.Tensor, out):
+    """pdelta_pack into the caller's ``out = (B_packed, v_row | None, v_col | None)`` with the
+    partial sums in the library's own scratch array: nothing is allocated, here or in the library."""
+    d_out, d_in = W_b.shape
+    if W_f.shape != W_b.shape or W_f.dtype != W_b.dtype:
+        raise ValueError("W_f and W_b must agree in shape and dtype")
+    B, v_row, v_col = out
+    rc = lib().pdelta_pack_noalloc(_dev(W_f, "W_f"), _dev(W_b, "W_b"), d_out, d_in, dtype_code(W_b.dtype),
+                                   _dev(B, "B_packed"),
+                                   _dev(v_row, "v_row") if v_row is not None else None,
+                                   _dev(v_col, "v_col") if v_col is not None else None, _stream())
+    _check(rc, "pdelta_pack_noalloc")
     return B, v_row, v_col
 
 

@@ -132,13 +132,14 @@ size_t pdelta_pack_workspace_bytes(int64_t d_out, int64_t d_in)
 
 static int pack_check(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, int w_dtype,
                       uint32_t* B_packed, uint16_t* v_row, uint16_t* v_col, void* workspace,
-                      size_t workspace_bytes)
+                      size_t workspace_bytes, bool own_scratch = false)
 {
     using namespace pdelta;
     if (W_f == nullptr || W_b == nullptr || B_packed == nullptr) return PDELTA_EINVAL;
     if (const int rc = check_dims(d_out, d_in)) return rc;
     if (!is_w_dtype(w_dtype)) return PDELTA_EDTYPE;
-    const bool want_scales = v_row != nullptr || v_col != nullptr;
+    // own_scratch: the partial sums go to the library's array, which no caller buffer can overlap
+    const bool want_scales = (v_row != nullptr || v_col != nullptr) && !own_scratch;
     if (want_scales && (workspace == nullptr || workspace_bytes < pdelta_pack_workspace_bytes(d_out, d_in)))
         return PDELTA_EWORKSPACE;
     if (misaligned(W_f) || misaligned(W_b) || misaligned(B_packed) || misaligned(v_row) ||
@@ -173,6 +174,29 @@ int pdelta_pack(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, i
         return rc;
     const int rc = launch_pack_dispatch(w_dtype, W_f, W_b, d_out, d_in, B_packed, v_row, v_col,
                                         workspace, (hipStream_t)stream);
+    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+}
+
+size_t pdelta_pack_noalloc_max_bytes(void) { return pdelta::kPackScratchBytes; }
+
+int pdelta_pack_noalloc(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, int w_dtype,
+                        uint32_t* B_packed, uint16_t* v_row, uint16_t* v_col, void* stream)
+{
+    using namespace pdelta;
+    const TuneScope tune_scope;
+    // Everything that can be decided on the host comes first: the checks of pdelta_pack with a
+    // stand-in scratch range that overlaps nothing, and the size limit of the library's array.
+    if (const int rc = pack_check(W_f, W_b, d_out, d_in, w_dtype, B_packed, v_row, v_col, nullptr, 0,
+                                  /*own_scratch=*/true))
+        return rc;
+    const bool want_scales = v_row != nullptr || v_col != nullptr;
+    void* ws = nullptr;
+    if (want_scales) {
+        if (pack_workspace_bytes(d_out, d_in) > kPackScratchBytes) return PDELTA_EWORKSPACE;
+        if (pack_static_scratch(&ws) != 0) return PDELTA_EHIP;
+    }
+    const int rc = launch_pack_dispatch(w_dtype, W_f, W_b, d_out, d_in, B_packed, v_row, v_col, ws,
+                                        (hipStream_t)stream);
     return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
 }
 

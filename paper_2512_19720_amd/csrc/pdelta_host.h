@@ -16,6 +16,11 @@ int launch_pack_dispatch(int w_dtype, const void* W_f, const void* W_b, int64_t 
                          int64_t d_in, uint32_t* B_packed, uint16_t* v_row, uint16_t* v_col,
                          void* workspace, hipStream_t stream);
 
+// Device address of the library's own scratch array (kPackScratchBytes, one copy per GPU) on the
+// current device; looked up once per device.  Returns 0, or -1 when the runtime refuses.
+constexpr size_t kPackScratchBytes = (size_t)16 << 20;
+int pack_static_scratch(void** ptr);
+
 // Batched pack: geometry helpers shared by the plan (host) and the launcher.
 int pack_batch_tile_blocks(int64_t d_out);
 int64_t pack_batch_tiles(int64_t d_out, int64_t d_in, int tile_blocks);

@@ -409,6 +409,33 @@ int launch_pack_batch(int w_dtype, const pdelta_pack_job* jobs_host, const pdelt
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// ---- scratch owned by the library, for callers that cannot allocate --------------------------
+// pdelta_pack_noalloc runs the kernels above with their partial sums in this array instead of a
+// caller's workspace.  Each GPU the library runs on holds its own copy at its own address until
+// the process ends.  The name below is a host-side stand-in, not a device address: the address is
+// asked for once per device (with that device current) and only that pointer is ever handed to
+// a kernel.  Nothing has to be cleared between calls: every slot a finalize kernel reads has been
+// written by the main kernel of the same call.
+static __device__ __align__(256) unsigned char scratch[kPackScratchBytes];
+
+int pack_static_scratch(void** ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static void* address_on_device[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    void* p = __atomic_load_n(&address_on_device[dev], __ATOMIC_ACQUIRE);
+    if (p == nullptr) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return -1;
+        }
+        __atomic_store_n(&address_on_device[dev], p, __ATOMIC_RELEASE);
+    }
+    *ptr = p;
+    return 0;
+}
+
 int launch_pack_dispatch(int w_dtype, const void* W_f, const void* W_b, int64_t d_out,
                          int64_t d_in, uint32_t* B_packed, uint16_t* v_row, uint16_t* v_col,
                          void* workspace, hipStream_t stream)
