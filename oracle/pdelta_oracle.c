@@ -31,7 +31,8 @@
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py (hand-written words,
  * exact rational arithmetic, closed forms, library matmul in the v = 0 case, brute force on
- * 4 x 8).  Nothing in this file is "parity unpinned".
+ * 4 x 8; the blockwise-scale functions also by their reductions to row mode, column mode and a
+ * constant scale).  Nothing in this file is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -295,6 +296,138 @@ int pdelta_grad_v_ref(const uint16_t* X, const uint16_t* dY, const uint32_t* B_p
         grad[a] = g;
     }
     return 0;
+}
+
+/* ---- blockwise ("per-group") and scalar scales -------------------------------------------------
+ * The paper names blockwise per-group scales as the first extension of the per-axis vectors
+ * (Conclusion) and compares against a single learned scalar per matrix (the BitDelta baseline
+ * of the Experiments section).  Both are the same Eq. 1, W_hat = v (.) B + W_b, with v constant
+ * over blocks of the matrix instead of along one whole axis:
+ *     scale(o, i) = v[ (v_rows == 1 ? 0 : o) * (d_in / group) + i / group ]
+ * v has v_rows x (d_in / group) entries; v_rows is d_out (one scale per output row and group of
+ * `group` consecutive inputs) or 1 (the rows share the scales).  Special cases:
+ *     v_rows = d_out, group = d_in   row mode            (one scale per output row)
+ *     v_rows = 1,     group = 1      column mode         (one scale per input)
+ *     v_rows = 1,     group = d_in   one scalar for the whole matrix
+ * group must divide d_in.  The initial value of each scale is the mean of |Delta W| over the
+ * entries it covers (the per-layer compression algorithm's initialisation, applied per block),
+ * rounded once to fp16.                                                                       */
+static int group_args_ok(int64_t d_out, int64_t d_in, int64_t group, int64_t v_rows)
+{
+    return d_out > 0 && d_in > 0 && group > 0 && d_in % group == 0 && (v_rows == 1 || v_rows == d_out);
+}
+
+static double group_scale(const uint16_t* v, int64_t o, int64_t i, int64_t d_in, int64_t group,
+                          int64_t v_rows)
+{
+    int64_t n_groups = d_in / group;
+    return decode_f16(v[(v_rows == 1 ? 0 : o) * n_groups + i / group]);
+}
+
+/* Signs as in pdelta_pack_ref, scales per block: v[r, g] = RNE_fp16(mean |W_f - W_b|) over the
+ * rows r covers (one row, or all of them when v_rows == 1) and inputs g*group .. g*group+group-1. */
+int pdelta_pack_group_ref(const uint16_t* W_f, const uint16_t* W_b, int64_t d_out, int64_t d_in,
+                          int w_dtype, int64_t group, int64_t v_rows, uint32_t* B_packed, uint16_t* v)
+{
+    if (!W_f || !W_b || !B_packed || !v || !group_args_ok(d_out, d_in, group, v_rows)) return REF_EINVAL;
+    int rc = pdelta_pack_ref(W_f, W_b, d_out, d_in, w_dtype, B_packed, NULL, NULL);
+    if (rc != REF_OK) return rc;
+    int64_t n_groups = d_in / group;
+    for (int64_t r = 0; r < v_rows; ++r)
+        for (int64_t g = 0; g < n_groups; ++g) {
+            int64_t o_first = v_rows == 1 ? 0 : r, o_last = v_rows == 1 ? d_out - 1 : r;
+            double sum = 0.0;
+            for (int64_t o = o_first; o <= o_last; ++o)
+                for (int64_t i = g * group; i < (g + 1) * group; ++i)
+                    sum += fabs(pdelta_ref_decode(W_f[o * d_in + i], w_dtype) -
+                                pdelta_ref_decode(W_b[o * d_in + i], w_dtype));
+            double count = (double)(o_last - o_first + 1) * (double)group;
+            v[r * n_groups + g] = pdelta_ref_rne_f16(sum / count);
+        }
+    return REF_OK;
+}
+
+/* W_hat = W_b + scale(o, i) * B (Eq. 1 with blockwise scales), exact in fp64. */
+int pdelta_patch_group_ref(const uint16_t* W_b, const uint32_t* B_packed, const uint16_t* v,
+                           int64_t group, int64_t v_rows, int64_t d_out, int64_t d_in, int w_dtype,
+                           double* W_hat)
+{
+    if (!W_b || !B_packed || !v || !W_hat || !group_args_ok(d_out, d_in, group, v_rows)) return REF_EINVAL;
+    int64_t wpr = words_per_row(d_in);
+    for (int64_t o = 0; o < d_out; ++o)
+        for (int64_t i = 0; i < d_in; ++i) {
+            double b = ((B_packed[o * wpr + i / 32] >> (i % 32)) & 1u) ? 1.0 : -1.0;
+            W_hat[o * d_in + i] = pdelta_ref_decode(W_b[o * d_in + i], w_dtype) +
+                                  group_scale(v, o, i, d_in, group, v_rows) * b;
+        }
+    return REF_OK;
+}
+
+/* The merged weights as stored: one RNE rounding of the exact sum to the weight dtype. */
+int pdelta_patch_group_round_ref(const uint16_t* W_b, const uint32_t* B_packed, const uint16_t* v,
+                                 int64_t group, int64_t v_rows, int64_t d_out, int64_t d_in,
+                                 int w_dtype, uint16_t* W_out)
+{
+    if (!W_out || d_out <= 0 || d_in <= 0) return REF_EINVAL;
+    double* W_hat = (double*)malloc((size_t)(d_out * d_in) * sizeof(double));
+    if (!W_hat) return REF_EINVAL;
+    int rc = pdelta_patch_group_ref(W_b, B_packed, v, group, v_rows, d_out, d_in, w_dtype, W_hat);
+    if (rc == REF_OK)
+        for (int64_t j = 0; j < d_out * d_in; ++j)
+            W_out[j] = w_dtype == REF_BF16 ? pdelta_ref_rne_bf16(W_hat[j]) : pdelta_ref_rne_f16(W_hat[j]);
+    free(W_hat);
+    return rc;
+}
+
+/* Y = X * W_hat^T with W_hat rebuilt densely from blockwise scales; Y is [M, d_out] fp64. */
+int pdelta_linear_group_ref(const uint16_t* X, const uint16_t* W_b, const uint32_t* B_packed,
+                            const uint16_t* v, int64_t group, int64_t v_rows, int64_t M,
+                            int64_t d_out, int64_t d_in, int x_dtype, double* Y)
+{
+    if (!X || !Y || M <= 0 || d_out <= 0 || d_in <= 0) return REF_EINVAL;
+    double* W_hat = (double*)malloc((size_t)(d_out * d_in) * sizeof(double));
+    double* Xd = (double*)malloc((size_t)(M * d_in) * sizeof(double));
+    if (!W_hat || !Xd) { free(W_hat); free(Xd); return REF_EINVAL; }
+    int rc = pdelta_patch_group_ref(W_b, B_packed, v, group, v_rows, d_out, d_in, x_dtype, W_hat);
+    if (rc == REF_OK) {
+        for (int64_t j = 0; j < M * d_in; ++j) Xd[j] = pdelta_ref_decode(X[j], x_dtype);
+#pragma omp parallel for schedule(static)
+        for (int64_t o = 0; o < d_out; ++o)
+            for (int64_t m = 0; m < M; ++m) {
+                double acc = 0.0;
+                for (int64_t i = 0; i < d_in; ++i) acc += Xd[m * d_in + i] * W_hat[o * d_in + i];
+                Y[m * d_out + o] = acc;
+            }
+    }
+    free(W_hat);
+    free(Xd);
+    return rc;
+}
+
+/* The same definition at chosen outputs only (layers too large to multiply whole). */
+int pdelta_linear_group_ref_at(const uint16_t* X, const uint16_t* W_b, const uint32_t* B_packed,
+                               const uint16_t* v, int64_t group, int64_t v_rows, int64_t M,
+                               int64_t d_out, int64_t d_in, int x_dtype, int64_t n,
+                               const int64_t* m_idx, const int64_t* o_idx, double* y)
+{
+    if (!X || !W_b || !B_packed || !v || !y || !m_idx || !o_idx) return REF_EINVAL;
+    if (M <= 0 || n < 0 || !group_args_ok(d_out, d_in, group, v_rows)) return REF_EINVAL;
+    int64_t wpr = words_per_row(d_in);
+    for (int64_t s = 0; s < n; ++s)
+        if (m_idx[s] < 0 || m_idx[s] >= M || o_idx[s] < 0 || o_idx[s] >= d_out) return REF_EINVAL;
+#pragma omp parallel for schedule(static)
+    for (int64_t s = 0; s < n; ++s) {
+        int64_t m = m_idx[s], o = o_idx[s];
+        double acc = 0.0;
+        for (int64_t i = 0; i < d_in; ++i) {
+            double b = ((B_packed[o * wpr + i / 32] >> (i % 32)) & 1u) ? 1.0 : -1.0;
+            double w_hat = pdelta_ref_decode(W_b[o * d_in + i], x_dtype) +
+                           group_scale(v, o, i, d_in, group, v_rows) * b;
+            acc += pdelta_ref_decode(X[m * d_in + i], x_dtype) * w_hat;
+        }
+        y[s] = acc;
+    }
+    return REF_OK;
 }
 
 /* Number of threads the parallel loops above will use (for the bench's "cores" field). */

@@ -70,6 +70,11 @@ def _load():
         lib.pdelta_linear_ref.argtypes = [vp, vp, vp, vp, i32, i64, i64, i64, i32, vp]
         lib.pdelta_linear_ref_at.argtypes = [vp, vp, vp, vp, i32, i64, i64, i64, i32, i64, vp, vp, vp]
         lib.pdelta_grad_v_ref.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, vp]
+        lib.pdelta_pack_group_ref.argtypes = [vp, vp, i64, i64, i32, i64, i64, vp, vp]
+        lib.pdelta_patch_group_ref.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, vp]
+        lib.pdelta_patch_group_round_ref.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, vp]
+        lib.pdelta_linear_group_ref.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, vp]
+        lib.pdelta_linear_group_ref_at.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, i64, vp, vp, vp]
         lib.pdelta_ref_threads.restype = i32
         _lib = lib
     return _lib
@@ -220,13 +225,93 @@ def grad_v(X, dY, B_packed, axis: int, dtype: int = F16) -> np.ndarray:
     return out
 
 
-def linear_variants(X, W_b, Bs, vs, axis: int, x_dtype: int = F16) -> np.ndarray:
+def linear_variants(X, W_b, Bs, vs, axis, x_dtype: int = F16) -> np.ndarray:
     """R requests that share W_b: row r of the result is the delta linear layer (Eq. 1 inside
-    the layer forward) of token X[r] with request r's own (Bs[r], vs[r]).  Written out as what it
-    is: R independent single-token layers, one call of `linear` each."""
+    the layer forward) of token X[r] with request r's own (Bs[r], vs[r]) and its own axis (the
+    per-layer Row/Col selection may have chosen differently for different fine-tunes of one
+    base); `axis` is one mode for all requests or a sequence with one mode per request.  Written
+    out as what it is: R independent single-token layers, one call of `linear` each."""
     X = _bits16(X)
-    rows = [linear(X[r:r + 1], W_b, Bs[r], vs[r], axis, x_dtype)[0] for r in range(X.shape[0])]
+    axes = [axis] * X.shape[0] if isinstance(axis, (int, np.integer)) else list(axis)
+    if len(axes) != X.shape[0]:
+        raise ValueError("one axis per request")
+    rows = [linear(X[r:r + 1], W_b, Bs[r], vs[r], axes[r], x_dtype)[0] for r in range(X.shape[0])]
     return np.stack(rows) if rows else np.zeros((0, _bits16(W_b).shape[0]))
+
+
+# ---- blockwise ("per-group") and scalar scales ----------------------------------------------
+# v is [v_rows, d_in // group] fp16 bits with v_rows = d_out (a scale per output row and group of
+# `group` consecutive inputs) or 1 (shared by all rows); v_rows = 1 with group = d_in is one
+# scalar for the whole matrix.
+
+def _group_args(W_b, B_packed, v, group):
+    wb = _bits16(W_b)
+    d_out, d_in = wb.shape
+    B = np.ascontiguousarray(B_packed, dtype=np.uint32)
+    vv = _bits16(v)
+    if B.shape != (d_out, words_per_row(d_in)):
+        raise ValueError("B_packed shape does not match W_b")
+    if group <= 0 or d_in % group != 0 or vv.ndim != 2 or vv.shape[1] != d_in // group or vv.shape[0] not in (1, d_out):
+        raise ValueError("v must be [d_out or 1, d_in // group] and group must divide d_in")
+    return wb, B, vv, d_out, d_in, vv.shape[0]
+
+
+def pack_group(W_f, W_b, group: int, shared_rows: bool = False, w_dtype: int = F16):
+    """(B_packed, v [d_out or 1, d_in // group] fp16 bits): signs as `pack`, v = mean |dW| per block."""
+    lib = _load()
+    wf, wb = _bits16(W_f), _bits16(W_b)
+    if wf.ndim != 2 or wf.shape != wb.shape:
+        raise ValueError("W_f and W_b must be 2-D and of equal shape")
+    d_out, d_in = wf.shape
+    if group <= 0 or d_in % group != 0:
+        raise ValueError("group must divide d_in")
+    v_rows = 1 if shared_rows else d_out
+    B = np.empty((d_out, words_per_row(d_in)), dtype=np.uint32)
+    v = np.empty((v_rows, d_in // group), dtype=np.uint16)
+    _check(lib.pdelta_pack_group_ref(_ptr(wf), _ptr(wb), d_out, d_in, w_dtype, group, v_rows, _ptr(B), _ptr(v)),
+           "pack_group")
+    return B, v
+
+
+def patch_group(W_b, B_packed, v, group: int, w_dtype: int = F16) -> np.ndarray:
+    """Exact fp64 W_hat = W_b + scale(o, i) B with blockwise scales."""
+    wb, B, vv, d_out, d_in, v_rows = _group_args(W_b, B_packed, v, group)
+    out = np.empty((d_out, d_in), dtype=np.float64)
+    _check(_load().pdelta_patch_group_ref(_ptr(wb), _ptr(B), _ptr(vv), group, v_rows, d_out, d_in, w_dtype,
+                                          _ptr(out)), "patch_group")
+    return out
+
+
+def patch_group_round(W_b, B_packed, v, group: int, w_dtype: int = F16) -> np.ndarray:
+    wb, B, vv, d_out, d_in, v_rows = _group_args(W_b, B_packed, v, group)
+    out = np.empty((d_out, d_in), dtype=np.uint16)
+    _check(_load().pdelta_patch_group_round_ref(_ptr(wb), _ptr(B), _ptr(vv), group, v_rows, d_out, d_in, w_dtype,
+                                                _ptr(out)), "patch_group_round")
+    return out
+
+
+def linear_group(X, W_b, B_packed, v, group: int, x_dtype: int = F16) -> np.ndarray:
+    """fp64 Y [M, d_out] = X W_hat^T with W_hat rebuilt densely from blockwise scales."""
+    wb, B, vv, d_out, d_in, v_rows = _group_args(W_b, B_packed, v, group)
+    x = _bits16(X)
+    if x.ndim != 2 or x.shape[1] != d_in:
+        raise ValueError("X must be [M, d_in]")
+    out = np.empty((x.shape[0], d_out), dtype=np.float64)
+    _check(_load().pdelta_linear_group_ref(_ptr(x), _ptr(wb), _ptr(B), _ptr(vv), group, v_rows, x.shape[0],
+                                           d_out, d_in, x_dtype, _ptr(out)), "linear_group")
+    return out
+
+
+def linear_group_at(X, W_b, B_packed, v, group: int, m_idx, o_idx, x_dtype: int = F16) -> np.ndarray:
+    wb, B, vv, d_out, d_in, v_rows = _group_args(W_b, B_packed, v, group)
+    x = _bits16(X)
+    mi = np.ascontiguousarray(m_idx, dtype=np.int64)
+    oi = np.ascontiguousarray(o_idx, dtype=np.int64)
+    out = np.empty(mi.shape, dtype=np.float64)
+    _check(_load().pdelta_linear_group_ref_at(_ptr(x), _ptr(wb), _ptr(B), _ptr(vv), group, v_rows, x.shape[0],
+                                              d_out, d_in, x_dtype, mi.size, _ptr(mi), _ptr(oi), _ptr(out)),
+           "linear_group_at")
+    return out
 
 
 def threads() -> int:

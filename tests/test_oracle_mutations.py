@@ -31,6 +31,12 @@ MUTATIONS = [
     ("fp16 rounding truncates", "uint16_t pdelta_ref_rne_f16(double x)  { return rne_generic(x, 10, -14, 15, 15); }",
      "uint16_t pdelta_ref_rne_f16(double x)  { return rne_generic(x * (1.0 - 1.0 / 4096.0), 10, -14, 15, 15); }",
      ["test_oracle_formats.py"]),
+    ("block scale indexed inside the group instead of by the group", "* n_groups + i / group]);",
+     "* n_groups + i % n_groups]);", ["test_oracle_group.py"]),
+    ("block scale ignores the output row", "return decode_f16(v[(v_rows == 1 ? 0 : o) * n_groups",
+     "return decode_f16(v[(v_rows == 1 ? 0 : 0) * n_groups", ["test_oracle_group.py"]),
+    ("block mean divided by the group size only", "double count = (double)(o_last - o_first + 1) * (double)group;",
+     "double count = (double)group;", ["test_oracle_group.py"]),
     ("gradient modes swapped", "if (axis == 0) {\n                double s = 0.0;", "if (axis == 1) {\n                double s = 0.0;",
      ["test_oracle_linear.py"]),
 ]
