@@ -49,8 +49,9 @@ typedef enum {
 } pdelta_dtype;
 
 typedef enum {
-    PDELTA_ROW = 0, /* v has d_out entries: W_hat[o,i] = W_b[o,i] + v[o] * B[o,i] */
-    PDELTA_COL = 1  /* v has d_in  entries: W_hat[o,i] = W_b[o,i] + v[i] * B[o,i] */
+    PDELTA_ROW = 0,        /* v has d_out entries: W_hat[o,i] = W_b[o,i] + v[o] * B[o,i] */
+    PDELTA_COL = 1,        /* v has d_in  entries: W_hat[o,i] = W_b[o,i] + v[i] * B[o,i] */
+    PDELTA_PER_REQUEST = 2 /* pdelta_linear_variants only: each request names its own axis */
 } pdelta_axis;
 
 typedef enum {
@@ -270,16 +271,26 @@ int pdelta_pack_batch(const pdelta_pack_job* jobs_host, const pdelta_pack_job* j
  * Arguments
  *   X         in   [R, d_in], dtype x_dtype; row r is the token of request r
  *   W_b       in   [d_out, d_in], same dtype
- *   variants  in   R records {B_packed [d_out, d_in/32], v FP16 [d_out] (row) or [d_in] (col)};
- *                  a HOST copy (validated here) and a DEVICE copy (read by the kernel) of the same
- *                  array, both owned by the caller and valid until the stream has run the call
- *   axis      PDELTA_ROW or PDELTA_COL, one mode for all requests of a call
+ *   variants  in   R records {B_packed [d_out, d_in/32], v FP16 [d_out] (row) or [d_in] (col),
+ *                  axis}; a HOST copy (validated here) and a DEVICE copy (read by the kernel) of
+ *                  the same array, both owned by the caller and valid until the stream has run
+ *                  the call
+ *   axis      PDELTA_ROW or PDELTA_COL: one mode for all requests of the call (the records' axis
+ *             fields are ignored); PDELTA_PER_REQUEST: request r uses variants[r].axis - the
+ *             per-layer Row/Col selection of the paper's compression algorithm may have chosen
+ *             differently for different fine-tunes of the same base layer
  *   Y         out  [R, d_out], dtype y_dtype; must not overlap any input
- * R = 0 is a no-op.  Errors as for pdelta_linear_row, per variant.
+ * When the requests of a PDELTA_PER_REQUEST call do not all share one axis, the sign part of
+ * every request is evaluated in fp16: column-mode requests as in pdelta_linear_col, row-mode
+ * requests with the operand fp16(X) (exact for fp16 X; for bf16 X exact for magnitudes in
+ * [2^-14, 65504]).  R = 0 is a no-op.  Errors as for pdelta_linear_row, per variant; a record
+ * axis other than PDELTA_ROW / PDELTA_COL gives PDELTA_EINVAL.
  */
 typedef struct pdelta_variant {
     const uint32_t* B_packed;
     const uint16_t* v;
+    int32_t axis;             /* PDELTA_ROW or PDELTA_COL; read when the call's axis is PDELTA_PER_REQUEST */
+    int32_t reserved;         /* set to 0 */
 } pdelta_variant;
 
 int pdelta_linear_variants(const void* X, const void* W_b, const pdelta_variant* variants_host,

@@ -12,7 +12,7 @@ import os
 import torch
 
 F16, BF16, F32 = 0, 1, 2
-ROW, COL = 0, 1
+ROW, COL, PER_REQUEST = 0, 1, 2
 
 OK, EINVAL, ESHAPE, EALIGN, EDTYPE, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5, -6
 
@@ -35,7 +35,8 @@ class Layer(ctypes.Structure):
 
 class Variant(ctypes.Structure):
     """Mirror of the C struct ``pdelta_variant``."""
-    _fields_ = [("B_packed", ctypes.c_void_p), ("v", ctypes.c_void_p)]
+    _fields_ = [("B_packed", ctypes.c_void_p), ("v", ctypes.c_void_p), ("axis", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 class PackJob(ctypes.Structure):
@@ -358,13 +359,19 @@ def pdelta_pack_batch(plan: PackPlan):
 class VariantSet:
     """Host and device copies of a ``pdelta_variant`` array plus the tensors they point to."""
 
-    def __init__(self, variants, axis: int):
+    def __init__(self, variants, axis):
+        """``variants``: R pairs (B_packed, v); ``axis``: ROW or COL for all of them, or a sequence
+        with one axis per request."""
         variants = list(variants)
-        self.axis = axis
+        per_request = not isinstance(axis, int)
+        axes = list(axis) if per_request else [axis] * len(variants)
+        if len(axes) != len(variants):
+            raise ValueError("one axis per variant")
+        self.axis = PER_REQUEST if per_request else axis
         self.tensors = variants
         self.host = (Variant * max(len(variants), 1))()
         for r, (B_packed, v) in enumerate(variants):
-            self.host[r] = Variant(_dev(B_packed, "B_packed"), _dev(v, "v"))
+            self.host[r] = Variant(_dev(B_packed, "B_packed"), _dev(v, "v"), int(axes[r]), 0)
         self.device = _to_device(self.host, variants[0][0].device) if variants else None
 
     def __len__(self):

@@ -29,7 +29,8 @@ def _hipcc() -> str:
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [_hipcc(), *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    extra = os.environ.get("PDELTA_EXTRA_HIPCC_FLAGS", "").split()      # developer builds (e.g. -D switches)
+    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"       # host pass ignores the GPU feature
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)

@@ -371,23 +371,33 @@ int pdelta_linear_variants(const void* X, const void* W_b, const pdelta_variant*
     if (R < 0) return PDELTA_EINVAL;
     if (R > 0 && (variants_host == nullptr || variants_device == nullptr)) return PDELTA_EINVAL;
     if (misaligned(variants_device)) return PDELTA_EALIGN;
+    if (axis != PDELTA_ROW && axis != PDELTA_COL && axis != PDELTA_PER_REQUEST) return PDELTA_EINVAL;
     if (R == 0) {
-        if (axis != PDELTA_ROW && axis != PDELTA_COL) return PDELTA_EINVAL;
         if (const int rc = check_dims(d_out, d_in)) return rc;
         if (!is_w_dtype(x_dtype) || !is_y_dtype(y_dtype)) return PDELTA_EDTYPE;
         return PDELTA_OK;
     }
+    // per-request axes: every record names its own mode; all equal -> the single-mode kernels
+    int kernel_axis = axis;
+    if (axis == PDELTA_PER_REQUEST) {
+        kernel_axis = variants_host[0].axis;
+        for (int32_t r = 0; r < R; ++r) {
+            if (variants_host[r].axis != PDELTA_ROW && variants_host[r].axis != PDELTA_COL) return PDELTA_EINVAL;
+            if (variants_host[r].axis != kernel_axis) kernel_axis = PDELTA_PER_REQUEST;
+        }
+    }
     for (int32_t r = 0; r < R; ++r)
         if (const int rc = linear_check(X, W_b, variants_host[r].B_packed, variants_host[r].v, Y, R, d_out, d_in,
-                                        x_dtype, y_dtype, axis))
+                                        x_dtype, y_dtype, axis == PDELTA_PER_REQUEST ? variants_host[r].axis : axis))
             return rc;
     hipStream_t s = (hipStream_t)stream;
-    int rc = launch_linear_variants(x_dtype, y_dtype, axis, X, W_b, variants_device, R, Y, d_out, d_in, s);
+    int rc = launch_linear_variants(x_dtype, y_dtype, kernel_axis, X, W_b, variants_device, R, Y, d_out, d_in, s);
     if (rc == 1) {                                                      // request by request
         rc = 0;
         const size_t ysz = y_dtype == PDELTA_F32 ? 4 : 2;
         for (int32_t r = 0; r < R && rc == 0; ++r)
-            rc = launch_linear_skinny(x_dtype, y_dtype, axis, (const char*)X + (size_t)r * d_in * 2, W_b,
+            rc = launch_linear_skinny(x_dtype, y_dtype, axis == PDELTA_PER_REQUEST ? variants_host[r].axis : axis,
+                                      (const char*)X + (size_t)r * d_in * 2, W_b,
                                       variants_host[r].B_packed, variants_host[r].v,
                                       (char*)Y + (size_t)r * d_out * ysz, 1, d_out, d_in, s);
     }

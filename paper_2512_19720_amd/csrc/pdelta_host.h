@@ -48,7 +48,8 @@ int launch_linear_skinny_batch(int x_dtype, int y_dtype, const ::pdelta_layer* l
                                hipStream_t stream);
 
 // R requests (one token each) that share W_b and each have their own delta (more than 16 requests
-// run in chunks of 16).  Returns 1 when the fused kernel does not apply (d_in % 128 != 0), else 0 / -1.
+// run in chunks of 16).  axis 0 / 1: one mode for all requests; 2: variants[r].axis per request.
+// Returns 1 when the fused kernel does not apply (d_in % 128 != 0), else 0 / -1.
 int launch_linear_variants(int x_dtype, int y_dtype, int axis, const void* X, const void* W_b,
                            const ::pdelta_variant* variants_device, int R, void* Y, int64_t d_out,
                            int64_t d_in, hipStream_t stream);

@@ -43,7 +43,9 @@ struct VarStep {
     uint4v sw[8];                // four sign words of this lane's row per request (not staged: <= 8)
 };
 
-// XDT: dtype of X and W_b.  AXIS as in the single-variant kernels.  NQ = 8 or 16 request slots
+// XDT: dtype of X and W_b.  AXIS as in the single-variant kernels, or 2: each request brings its
+// own axis (variants[r].axis); the sign part then runs in fp16 with the operand fp16(x * v_r) for
+// column-mode requests and fp16(x * 1) for row-mode ones.  NQ = 8 or 16 request slots
 // (R <= NQ).  STAGE: the sign slabs of all requests are copied to LDS first.
 template <int XDT, int AXIS, int NQ, bool STAGE>
 __global__ void __launch_bounds__(512, 2)
@@ -79,7 +81,10 @@ linear_variants_kernel(const uint16_t* __restrict__ X, const uint16_t* __restric
     const int req = min(n, R - 1);
     const uint16_t* wrow = W_b + (int64_t)o * K + g * 8;
     const uint16_t* xrow = X + (int64_t)req * K + g * 8;
-    const uint16_t* vrow = AXIS == 1 ? variants[req].v + g * 8 : nullptr;
+    // per-request axis: a row-mode request has no scale per input; its loads of "v" read its own
+    // X row instead (valid memory of the right length) and the value is replaced by 1.0
+    const bool col = AXIS == 1 || (AXIS == 2 && variants[req].axis == PDELTA_COL);
+    const uint16_t* vrow = AXIS == 0 ? nullptr : (col ? variants[req].v + g * 8 : xrow);
     static_assert(STAGE || NQ == 8, "without staging a step keeps the sign words of 8 requests in registers");
     const uint32_t* brow[NQ];                         // this lane's sign row per request
     const int spr = wpr + 4;                          // LDS row stride in words (STAGE)
@@ -95,7 +100,7 @@ linear_variants_kernel(const uint16_t* __restrict__ X, const uint16_t* __restric
         for (int j = 0; j < 4; ++j) {
             S.w[j] = *(const uint4v*)(wrow + kb + j * 32);
             S.x[j] = *(const uint4v*)(xrow + kb + j * 32);
-            if constexpr (AXIS == 1) S.vc[j] = *(const uint4v*)(vrow + kb + j * 32);
+            if constexpr (AXIS != 0) S.vc[j] = *(const uint4v*)(vrow + kb + j * 32);
         }
         if constexpr (!STAGE) {
 #pragma unroll
@@ -116,15 +121,16 @@ linear_variants_kernel(const uint16_t* __restrict__ X, const uint16_t* __restric
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             xs[j] = S.x[j];
-            if constexpr (AXIS == 1) {                // sign-part operand: fp16(x * v_r)
+            if constexpr (AXIS != 0) {                // sign-part operand: fp16(x * v_r)
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
+                    const uint32_t vp = col ? (uint32_t)S.vc[j][p] : 0x3C003C00u;      // row-mode request: 1.0
                     if constexpr (XDT == kF16) {
-                        const uint32_t xp = S.x[j][p], vp = S.vc[j][p];
+                        const uint32_t xp = S.x[j][p];
                         xs[j][p] = as_u32(as_half2(xp) * as_half2(vp));
                     } else {
-                        const float lo = bf16_bits_to_f32(S.x[j][p] & 0xFFFFu) * f16_bits_to_f32(S.vc[j][p] & 0xFFFFu);
-                        const float hi = bf16_bits_to_f32(S.x[j][p] >> 16) * f16_bits_to_f32(S.vc[j][p] >> 16);
+                        const float lo = bf16_bits_to_f32(S.x[j][p] & 0xFFFFu) * f16_bits_to_f32(vp & 0xFFFFu);
+                        const float hi = bf16_bits_to_f32(S.x[j][p] >> 16) * f16_bits_to_f32(vp >> 16);
                         xs[j][p] = f32_to_f16_bits(lo) | (f32_to_f16_bits(hi) << 16);
                     }
                 }
@@ -235,7 +241,7 @@ linear_variants_kernel(const uint16_t* __restrict__ X, const uint16_t* __restric
                 delta += red_s[w][t < NQ ? t : 0][nn];
             }
             float scale = 1.0f;
-            if constexpr (AXIS == 0) scale = f16_bits_to_f32(variants[t].v[oo]);
+            if (AXIS == 0 || (AXIS == 2 && variants[t].axis == PDELTA_ROW)) scale = f16_bits_to_f32(variants[t].v[oo]);
             const float sum = base + scale * delta;
             const int64_t yi = (int64_t)t * d_out + oo;
             if (y_dtype == kF32) store_y<kF32>(Y, yi, sum);
@@ -295,11 +301,13 @@ int launch_linear_variants(int x_dtype, int y_dtype, int axis, const void* X, co
                            int64_t d_in, hipStream_t stream)
 {
     if (d_in % 128 != 0 || tune_value("variants_fused", 1) == 0) return 1;
-    if (x_dtype == kBF16)
-        return axis == 0 ? launch_variants<kBF16, 0>(X, W_b, variants_device, R, Y, d_out, d_in, y_dtype, stream)
-                         : launch_variants<kBF16, 1>(X, W_b, variants_device, R, Y, d_out, d_in, y_dtype, stream);
-    return axis == 0 ? launch_variants<kF16, 0>(X, W_b, variants_device, R, Y, d_out, d_in, y_dtype, stream)
-                     : launch_variants<kF16, 1>(X, W_b, variants_device, R, Y, d_out, d_in, y_dtype, stream);
+#define PDELTA_VAR(XDT)                                                                                         \
+    return axis == 0   ? launch_variants<XDT, 0>(X, W_b, variants_device, R, Y, d_out, d_in, y_dtype, stream)  \
+           : axis == 1 ? launch_variants<XDT, 1>(X, W_b, variants_device, R, Y, d_out, d_in, y_dtype, stream)  \
+                       : launch_variants<XDT, 2>(X, W_b, variants_device, R, Y, d_out, d_in, y_dtype, stream)
+    if (x_dtype == kBF16) PDELTA_VAR(kBF16);
+    PDELTA_VAR(kF16);
+#undef PDELTA_VAR
 }
 
 }  // namespace pdelta

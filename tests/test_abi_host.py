@@ -256,6 +256,13 @@ def test_linear_variants_argument_errors():
     assert run(variants(v=None)) == pd.EINVAL
     assert run(variants(v=A + 0x3000002)) == pd.EALIGN
     assert run(variants(B_packed=A + 0x4000000)) == pd.EINVAL         # Y overlaps a variant's signs
+    # one axis per request: every record must name ROW or COL; R = 0 stays a no-op
+    assert run(ok, R=0, axis=pd.PER_REQUEST) == pd.OK
+    assert run(variants(axis=2), axis=pd.PER_REQUEST) == pd.EINVAL
+    assert run(variants(axis=-1), axis=pd.PER_REQUEST) == pd.EINVAL
+    assert run(variants(axis=7), axis=pd.ROW, R=0) == pd.OK            # ignored when the call names the axis
+    # a column-mode record's v has d_in entries: Y placed inside that (longer) range is an overlap
+    assert run(variants(axis=pd.COL), axis=pd.PER_REQUEST, Y=A + 0x3010000 + 128, d_out=64, d_in=128) == pd.EINVAL
 
 
 def test_grad_v_workspace_and_argument_errors():
@@ -361,15 +368,16 @@ int main(void) {
            offsetof(pdelta_layer, X), offsetof(pdelta_layer, W_b), offsetof(pdelta_layer, B_packed),
            offsetof(pdelta_layer, v), offsetof(pdelta_layer, Y), offsetof(pdelta_layer, d_out),
            offsetof(pdelta_layer, d_in), offsetof(pdelta_layer, axis), offsetof(pdelta_layer, first_block));
-    printf("pdelta_variant %zu %zu %zu\n", sizeof(pdelta_variant), offsetof(pdelta_variant, B_packed),
-           offsetof(pdelta_variant, v));
+    printf("pdelta_variant %zu %zu %zu %zu %zu\n", sizeof(pdelta_variant), offsetof(pdelta_variant, B_packed),
+           offsetof(pdelta_variant, v), offsetof(pdelta_variant, axis), offsetof(pdelta_variant, reserved));
     printf("pdelta_pack_job %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\n", sizeof(pdelta_pack_job),
            offsetof(pdelta_pack_job, W_f), offsetof(pdelta_pack_job, W_b), offsetof(pdelta_pack_job, B_packed),
            offsetof(pdelta_pack_job, v_row), offsetof(pdelta_pack_job, v_col), offsetof(pdelta_pack_job, workspace),
            offsetof(pdelta_pack_job, workspace_bytes), offsetof(pdelta_pack_job, d_out), offsetof(pdelta_pack_job, d_in),
            offsetof(pdelta_pack_job, first_tile), offsetof(pdelta_pack_job, first_fin_block),
            offsetof(pdelta_pack_job, tile_blocks));
-    printf("enums %d %d %d %d %d %d\n", PDELTA_F16, PDELTA_BF16, PDELTA_F32, PDELTA_ROW, PDELTA_COL, PDELTA_EHIP);
+    printf("enums %d %d %d %d %d %d %d\n", PDELTA_F16, PDELTA_BF16, PDELTA_F32, PDELTA_ROW, PDELTA_COL, PDELTA_EHIP,
+           PDELTA_PER_REQUEST);
     return 0;
 }
 ''')
@@ -384,8 +392,8 @@ int main(void) {
 
     assert list(map(int, lines["pdelta_layer"].split())) == layout(
         pd.Layer, ["X", "W_b", "B_packed", "v", "Y", "d_out", "d_in", "axis", "first_block"])
-    assert list(map(int, lines["pdelta_variant"].split())) == layout(pd.Variant, ["B_packed", "v"])
+    assert list(map(int, lines["pdelta_variant"].split())) == layout(pd.Variant, ["B_packed", "v", "axis", "reserved"])
     assert list(map(int, lines["pdelta_pack_job"].split())) == layout(
         pd.PackJob, ["W_f", "W_b", "B_packed", "v_row", "v_col", "workspace", "workspace_bytes", "d_out", "d_in",
                      "first_tile", "first_fin_block", "tile_blocks"])
-    assert list(map(int, lines["enums"].split())) == [pd.F16, pd.BF16, pd.F32, pd.ROW, pd.COL, pd.EHIP]
+    assert list(map(int, lines["enums"].split())) == [pd.F16, pd.BF16, pd.F32, pd.ROW, pd.COL, pd.EHIP, pd.PER_REQUEST]

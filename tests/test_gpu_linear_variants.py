@@ -85,6 +85,49 @@ def test_request_by_request_fallback(R, d_in):
     check_y(Y, ref, f"fallback R={R} d_in={d_in}")
 
 
+def make_mixed(d_out, d_in, axes, dtype, seed):
+    """Shared base + one delta per request, request r in mode axes[r]."""
+    R = len(axes)
+    base = synth.layer_host(d_out, d_in, R, dtype, "row", seed)
+    Bs, vs = [], []
+    for r, axis in enumerate(axes):
+        Lr = synth.layer_host(d_out, d_in, 1, dtype, "row" if axis == orc.ROW else "col", seed + 2000 + r)
+        B, v_row, v_col = orc.pack(Lr["dW"], np.zeros_like(Lr["dW"]), dtype)
+        Bs.append(B)
+        vs.append(v_row if axis == orc.ROW else v_col)
+    dev = {"X": to_dev(base["X"], dtype), "W_b": to_dev(base["W_b"], dtype),
+           "variants": [(words_dev(B), f16_dev(v)) for B, v in zip(Bs, vs)]}
+    return base["X"], base["W_b"], Bs, vs, dev
+
+
+@pytest.mark.parametrize("R", [3, 16, 21])
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_one_axis_per_request(R, dtype, monkeypatch):
+    rng = np.random.default_rng(40 + R)
+    axes = [int(a) for a in rng.integers(0, 2, R)]
+    axes[0], axes[1] = orc.ROW, orc.COL                                # both modes are present
+    for d_out, d_in, tune in ((100, 1152, ""), (64, 4096, ""), (40, 384, "var_stage=0"), (48, 160, "")):
+        monkeypatch.setenv("PDELTA_TUNE", tune)                        # fused (staged / in registers) and fallback paths
+        X, W_b, Bs, vs, d = make_mixed(d_out, d_in, axes, dtype, synth.seed_for(1, 7000 + R + d_out))
+        ref = orc.linear_variants(X, W_b, Bs, vs, axes, dtype)
+        vset = pd.VariantSet(d["variants"], axes)
+        assert vset.axis == pd.PER_REQUEST
+        for yd in (torch.float32, torch.float16 if dtype == synth.F16 else torch.bfloat16):
+            Y = torch.full((R, d_out), float("nan"), dtype=yd, device=DEV)
+            pd.pdelta_linear_variants(d["X"], d["W_b"], vset, out=Y)
+            torch.cuda.synchronize()
+            check_y(Y, ref, f"mixed axes R={R} {d_out}x{d_in} dt={dtype} y={yd} tune={tune!r}")
+
+
+def test_per_request_axes_that_all_agree_use_the_single_mode_kernels():
+    for axis in (orc.ROW, orc.COL):
+        X, W_b, Bs, vs, d = make_variants(64, 512, 5, synth.F16, axis, 91)
+        one = pd.pdelta_linear_variants(d["X"], d["W_b"], pd.VariantSet(d["variants"], axis), out_dtype=torch.float32)
+        per = pd.pdelta_linear_variants(d["X"], d["W_b"], pd.VariantSet(d["variants"], [axis] * 5), out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert torch.equal(one, per)
+
+
 def test_identical_variants_equal_the_ordinary_layer():
     X, W_b, Bs, vs, d = make_variants(128, 512, 6, synth.F16, orc.ROW, 77)
     vset = pd.VariantSet([d["variants"][2]] * 6, orc.ROW)
