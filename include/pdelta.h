@@ -320,6 +320,42 @@ int pdelta_grad_v(const void* X, const void* dY, const uint32_t* B_packed, int a
                   int64_t M, int64_t d_out, int64_t d_in, int dtype, void* workspace,
                   size_t workspace_bytes, void* stream);
 
+/*
+ * Blockwise ("per-group") and scalar scales: Eq. 1 with v constant over blocks of the matrix
+ * instead of along one whole axis.  The paper's conclusion names blockwise per-group scales as
+ * its first extension, and its comparison baseline (Experiments section, the BitDelta rows of
+ * the results tables) is the case of one scalar per matrix.
+ *   scale(o, i) = v[ (shared_rows ? 0 : o) * (d_in / group) + i / group ]
+ *   W_hat[o,i]  = W_b[o,i] + scale(o, i) * B[o,i]
+ * v is FP16 [d_out or 1, d_in / group]: one scale per output row and group of `group` consecutive
+ * inputs, or (shared_rows = 1) one per group for all rows.  shared_rows = 1 with group = d_in is
+ * ONE scalar for the whole matrix; shared_rows = 0 with group = d_in is row mode.
+ * `group` must be d_in itself, or a power of two >= 32 that divides d_in (PDELTA_ESHAPE
+ * otherwise); shared_rows must be 0 or 1 (PDELTA_EINVAL).  Everything else (pointers, layouts,
+ * dtypes, alignment, aliasing, error codes, arithmetic and operand ranges) is as for the
+ * per-axis entry points: pdelta_linear_group as pdelta_linear_row except that for M <= 64 the
+ * sign part is multiplied in fp16 with the exact operands fp16(X) and +-v (for bf16 X exact for
+ * magnitudes in [2^-14, 65504]); pdelta_patch_group as pdelta_patch (exact sum, one rounding,
+ * in place allowed); pdelta_pack_group as pdelta_pack with
+ *   v[r, g] = mean |W_f - W_b| over the rows r covers and inputs g*group .. g*group + group - 1,
+ * the exact mean rounded once to FP16 (bit-equal to the fp64 reference for FP16 inputs while a
+ * block's sum of |dW| stays below 2^29).  Its workspace (pdelta_pack_group_workspace_bytes; 0
+ * unless shared_rows) holds one fp64 partial sum per row and group; contents on entry ignored.
+ */
+size_t pdelta_pack_group_workspace_bytes(int64_t d_out, int64_t d_in, int64_t group, int shared_rows);
+
+int pdelta_pack_group(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, int w_dtype,
+                      int64_t group, int shared_rows, uint32_t* B_packed, uint16_t* v,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+int pdelta_linear_group(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
+                        int64_t group, int shared_rows, void* Y, int64_t M, int64_t d_out,
+                        int64_t d_in, int x_dtype, int y_dtype, void* stream);
+
+int pdelta_patch_group(const void* W_b, const uint32_t* B_packed, const uint16_t* v, int64_t group,
+                       int shared_rows, void* W_out, int64_t d_out, int64_t d_in, int w_dtype,
+                       void* stream);
+
 /* Static, human-readable name of a pdelta_status value. */
 const char* pdelta_status_string(int status);
 

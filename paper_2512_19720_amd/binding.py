@@ -89,6 +89,14 @@ def lib() -> ctypes.CDLL:
         L.pdelta_grad_v_workspace_bytes.argtypes = [i64, i64, i64, i32]
         L.pdelta_grad_v.restype = i32
         L.pdelta_grad_v.argtypes = [vp, vp, vp, i32, vp, i64, i64, i64, i32, vp, sz, vp]
+        L.pdelta_pack_group_workspace_bytes.restype = sz
+        L.pdelta_pack_group_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.pdelta_pack_group.restype = i32
+        L.pdelta_pack_group.argtypes = [vp, vp, i64, i64, i32, i64, i32, vp, vp, vp, sz, vp]
+        L.pdelta_linear_group.restype = i32
+        L.pdelta_linear_group.argtypes = [vp, vp, vp, vp, i64, i32, vp, i64, i64, i64, i32, i32, vp]
+        L.pdelta_patch_group.restype = i32
+        L.pdelta_patch_group.argtypes = [vp, vp, vp, i64, i32, vp, i64, i64, i32, vp]
         L.pdelta_status_string.restype = ctypes.c_char_p
         L.pdelta_status_string.argtypes = [i32]
         _lib = L
@@ -413,4 +421,58 @@ def pdelta_grad_v(X, dY, B_packed, axis: int, out=None, workspace: torch.Tensor 
                              _dev(out, "grad_v"), M, d_out, d_in, dtype_code(X.dtype), _dev(workspace, "workspace"),
                              workspace.numel(), _stream())
     _check(rc, "pdelta_grad_v")
+    return out
+
+
+# ---- blockwise ("per-group") and scalar scales ----------------------------------------------
+# v is fp16 [d_out or 1, d_in // group]; one row means the scales are shared by all output rows
+# (with group = d_in: one scalar for the whole matrix).
+
+def _group_args(W_b, v, group: int):
+    d_out, d_in = W_b.shape
+    if v.dim() != 2 or v.shape[1] * group != d_in or v.shape[0] not in (1, d_out):
+        raise ValueError("v must be [d_out or 1, d_in // group]")
+    return d_out, d_in, int(v.shape[0] == 1 and d_out != 1)
+
+
+def pdelta_pack_group(W_f: torch.Tensor, W_b: torch.Tensor, group: int, shared_rows: bool = False):
+    """(B_packed int32 [d_out, d_in/32], v fp16 [d_out or 1, d_in // group])."""
+    d_out, d_in = W_b.shape
+    if W_f.shape != W_b.shape or W_f.dtype != W_b.dtype:
+        raise ValueError("W_f and W_b must agree in shape and dtype")
+    dev = W_b.device
+    B = torch.empty((d_out, d_in // 32), dtype=torch.int32, device=dev)
+    v = torch.empty((1 if shared_rows else d_out, max(d_in // max(group, 1), 1)), dtype=torch.float16, device=dev)
+    need = int(lib().pdelta_pack_group_workspace_bytes(d_out, d_in, group, int(shared_rows)))
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    rc = lib().pdelta_pack_group(_dev(W_f, "W_f"), _dev(W_b, "W_b"), d_out, d_in, dtype_code(W_b.dtype), group,
+                                 int(shared_rows), _dev(B, "B_packed"), _dev(v, "v"), _dev(ws, "workspace"),
+                                 ws.numel(), _stream())
+    _check(rc, "pdelta_pack_group")
+    return B, v
+
+
+def pdelta_linear_group(X, W_b, B_packed, v, group: int, out=None, out_dtype=None):
+    """Y = X W_hat^T with W_hat = W_b + scale(o, i) B and blockwise scales v."""
+    M, d_in = X.shape
+    d_out, _, shared = _group_args(W_b, v, group)
+    if W_b.shape[1] != d_in or X.dtype != W_b.dtype:
+        raise ValueError("X and W_b must agree in d_in and dtype")
+    if out is None:
+        out = torch.empty((M, d_out), dtype=out_dtype or X.dtype, device=X.device)
+    rc = lib().pdelta_linear_group(_dev(X, "X") or None, _dev(W_b, "W_b"), _dev(B_packed, "B_packed"), _dev(v, "v"),
+                                   group, shared, _dev(out, "Y") or None, M, d_out, d_in, dtype_code(X.dtype),
+                                   dtype_code(out.dtype), _stream())
+    _check(rc, "pdelta_linear_group")
+    return out
+
+
+def pdelta_patch_group(W_b, B_packed, v, group: int, out=None):
+    """W_out = round(W_b + scale(o, i) B); pass out=W_b to merge in place."""
+    d_out, d_in, shared = _group_args(W_b, v, group)
+    if out is None:
+        out = torch.empty_like(W_b)
+    rc = lib().pdelta_patch_group(_dev(W_b, "W_b"), _dev(B_packed, "B_packed"), _dev(v, "v"), group, shared,
+                                  _dev(out, "W_out"), d_out, d_in, dtype_code(W_b.dtype), _stream())
+    _check(rc, "pdelta_patch_group")
     return out

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libpdelta.so")
 
-SOURCES = ["pdelta_api.hip", "pdelta_pack.hip", "pdelta_patch.hip", "pdelta_linear_skinny.hip",
+SOURCES = ["pdelta_api.hip", "pdelta_pack.hip", "pdelta_pack_group.hip", "pdelta_patch.hip", "pdelta_linear_skinny.hip",
            "pdelta_linear_gemm.hip", "pdelta_linear_variants.hip", "pdelta_grad.hip"]
 
 HIPCC_FLAGS = [

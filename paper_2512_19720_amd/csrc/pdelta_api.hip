@@ -437,6 +437,113 @@ int pdelta_grad_v(const void* X, const void* dY, const uint32_t* B_packed, int a
     return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
 }
 
+// ---- blockwise ("per-group") and scalar scales -------------------------------------------------
+
+// Layout of a blockwise scale array for these arguments, or an error code.
+static int group_layout(int64_t d_out, int64_t d_in, int64_t group, int shared_rows, int* v_stride, int* g_shift,
+                        size_t* v_bytes)
+{
+    if (const int rc = pdelta::check_dims(d_out, d_in)) return rc;
+    if (group <= 0 || (shared_rows != 0 && shared_rows != 1)) return PDELTA_EINVAL;
+    int64_t n_groups = 1;
+    int shift = 31;                                     // one group spans the row: index 0 for every input
+    if (group != d_in) {
+        if (group < 32 || (group & (group - 1)) != 0 || d_in % group != 0) return PDELTA_ESHAPE;
+        shift = __builtin_ctzll((unsigned long long)group);
+        n_groups = d_in / group;
+    }
+    *v_stride = shared_rows ? 0 : (int)n_groups;
+    *g_shift = shift;
+    *v_bytes = (size_t)(shared_rows ? 1 : d_out) * (size_t)n_groups * 2;
+    return PDELTA_OK;
+}
+
+size_t pdelta_pack_group_workspace_bytes(int64_t d_out, int64_t d_in, int64_t group, int shared_rows)
+{
+    int v_stride, g_shift;
+    size_t v_bytes;
+    if (group_layout(d_out, d_in, group, shared_rows, &v_stride, &g_shift, &v_bytes) != PDELTA_OK) return 0;
+    return pdelta::pack_group_workspace_bytes(d_out, d_in, group, shared_rows);
+}
+
+int pdelta_pack_group(const void* W_f, const void* W_b, int64_t d_out, int64_t d_in, int w_dtype, int64_t group,
+                      int shared_rows, uint32_t* B_packed, uint16_t* v, void* workspace, size_t workspace_bytes,
+                      void* stream)
+{
+    using namespace pdelta;
+    const TuneScope tune_scope;
+    if (W_f == nullptr || W_b == nullptr || B_packed == nullptr || v == nullptr) return PDELTA_EINVAL;
+    int v_stride, g_shift;
+    size_t v_bytes;
+    if (const int rc = group_layout(d_out, d_in, group, shared_rows, &v_stride, &g_shift, &v_bytes)) return rc;
+    if (!is_w_dtype(w_dtype)) return PDELTA_EDTYPE;
+    const size_t need = pack_group_workspace_bytes(d_out, d_in, group, shared_rows);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return PDELTA_EWORKSPACE;
+    if (misaligned(W_f) || misaligned(W_b) || misaligned(B_packed) || misaligned(v) ||
+        (need > 0 && misaligned(workspace)))
+        return PDELTA_EALIGN;
+    const size_t w_bytes = (size_t)d_out * d_in * 2, b_bytes = w_bytes / 16;
+    struct Range { const void* p; size_t n; };
+    const Range in[2] = {{W_f, w_bytes}, {W_b, w_bytes}};
+    const Range out[3] = {{B_packed, b_bytes}, {v, v_bytes}, {need > 0 ? workspace : nullptr, need > 0 ? workspace_bytes : 0}};
+    for (int a = 0; a < 3; ++a) {
+        if (out[a].n == 0) continue;
+        for (int b = 0; b < 2; ++b)
+            if (overlaps(out[a].p, out[a].n, in[b].p, in[b].n)) return PDELTA_EINVAL;
+        for (int b = a + 1; b < 3; ++b)
+            if (out[b].n != 0 && overlaps(out[a].p, out[a].n, out[b].p, out[b].n)) return PDELTA_EINVAL;
+    }
+    const int rc = launch_pack_group(w_dtype, W_f, W_b, d_out, d_in, group, shared_rows, B_packed, v, workspace,
+                                     (hipStream_t)stream);
+    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+}
+
+int pdelta_linear_group(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v, int64_t group,
+                        int shared_rows, void* Y, int64_t M, int64_t d_out, int64_t d_in, int x_dtype, int y_dtype,
+                        void* stream)
+{
+    using namespace pdelta;
+    const TuneScope tune_scope;
+    if (W_b == nullptr || B_packed == nullptr || v == nullptr || M < 0) return PDELTA_EINVAL;
+    if (M > 0 && (X == nullptr || Y == nullptr)) return PDELTA_EINVAL;
+    int v_stride, g_shift;
+    size_t v_bytes;
+    if (const int rc = group_layout(d_out, d_in, group, shared_rows, &v_stride, &g_shift, &v_bytes)) return rc;
+    if (M > kMaxTokens) return PDELTA_ESHAPE;
+    if (!is_w_dtype(x_dtype) || !is_y_dtype(y_dtype)) return PDELTA_EDTYPE;
+    if (misaligned(X) || misaligned(W_b) || misaligned(B_packed) || misaligned(v) || misaligned(Y)) return PDELTA_EALIGN;
+    if (M == 0) return PDELTA_OK;
+    const size_t y_bytes = (size_t)M * d_out * (y_dtype == PDELTA_F32 ? 4 : 2);
+    if (overlaps(Y, y_bytes, X, (size_t)M * d_in * 2) || overlaps(Y, y_bytes, W_b, (size_t)d_out * d_in * 2) ||
+        overlaps(Y, y_bytes, B_packed, (size_t)d_out * d_in / 8) || overlaps(Y, y_bytes, v, v_bytes))
+        return PDELTA_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int rc = M <= kSkinnyMaxM ? launch_linear_skinny_group(x_dtype, y_dtype, X, W_b, B_packed, v, Y, M, d_out,
+                                                                 d_in, v_stride, g_shift, s)
+                                    : launch_linear_gemm_group(x_dtype, y_dtype, X, W_b, B_packed, v, Y, M, d_out,
+                                                               d_in, v_stride, g_shift, s);
+    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+}
+
+int pdelta_patch_group(const void* W_b, const uint32_t* B_packed, const uint16_t* v, int64_t group, int shared_rows,
+                       void* W_out, int64_t d_out, int64_t d_in, int w_dtype, void* stream)
+{
+    using namespace pdelta;
+    const TuneScope tune_scope;
+    if (W_b == nullptr || B_packed == nullptr || v == nullptr || W_out == nullptr) return PDELTA_EINVAL;
+    int v_stride, g_shift;
+    size_t v_bytes;
+    if (const int rc = group_layout(d_out, d_in, group, shared_rows, &v_stride, &g_shift, &v_bytes)) return rc;
+    if (!is_w_dtype(w_dtype)) return PDELTA_EDTYPE;
+    if (misaligned(W_b) || misaligned(B_packed) || misaligned(v) || misaligned(W_out)) return PDELTA_EALIGN;
+    const size_t w_bytes = (size_t)d_out * d_in * 2;
+    if (W_out != W_b && overlaps(W_out, w_bytes, W_b, w_bytes)) return PDELTA_EINVAL;
+    if (overlaps(W_out, w_bytes, B_packed, w_bytes / 16) || overlaps(W_out, w_bytes, v, v_bytes)) return PDELTA_EINVAL;
+    const int rc = launch_patch_group(w_dtype, W_b, B_packed, v, W_out, d_out, d_in, v_stride, g_shift,
+                                      (hipStream_t)stream);
+    return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
+}
+
 const char* pdelta_status_string(int status)
 {
     switch (status) {

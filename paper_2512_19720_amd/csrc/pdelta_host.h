@@ -41,6 +41,24 @@ int launch_linear_skinny(int x_dtype, int y_dtype, int axis, const void* X, cons
                          const uint32_t* B_packed, const uint16_t* v, void* Y, int64_t M,
                          int64_t d_out, int64_t d_in, hipStream_t stream);
 
+// The same with blockwise scales v[row * v_stride + (input >> g_shift)] (v_stride = 0: the rows
+// share the scales; g_shift = 31: one group spans all of d_in).
+int launch_linear_skinny_group(int x_dtype, int y_dtype, const void* X, const void* W_b,
+                               const uint32_t* B_packed, const uint16_t* v, void* Y, int64_t M,
+                               int64_t d_out, int64_t d_in, int v_stride, int g_shift, hipStream_t stream);
+int launch_linear_gemm_group(int x_dtype, int y_dtype, const void* X, const void* W_b,
+                             const uint32_t* B_packed, const uint16_t* v, void* Y, int64_t M,
+                             int64_t d_out, int64_t d_in, int v_stride, int g_shift, hipStream_t stream);
+int launch_patch_group(int w_dtype, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
+                       void* W_out, int64_t d_out, int64_t d_in, int v_stride, int g_shift,
+                       hipStream_t stream);
+// pack with blockwise scales: signs + fp64 block sums (per row), then the scales; `workspace` is
+// needed only when the rows share the scales (one partial sum per row and group).
+size_t pack_group_workspace_bytes(int64_t d_out, int64_t d_in, int64_t group, int shared_rows);
+int launch_pack_group(int w_dtype, const void* W_f, const void* W_b, int64_t d_out, int64_t d_in,
+                      int64_t group, int shared_rows, uint32_t* B_packed, uint16_t* v, void* workspace,
+                      hipStream_t stream);
+
 // Several decode-shaped layers in one launch.  Returns 1 when the batched kernel does not apply
 // (the caller then launches layer by layer), else 0 / -1.
 int launch_linear_skinny_batch(int x_dtype, int y_dtype, const ::pdelta_layer* layers_host,

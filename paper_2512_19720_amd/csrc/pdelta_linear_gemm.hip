@@ -112,7 +112,7 @@ __global__ void __launch_bounds__(WM * 128, (WM * 128) / 128)
 linear_gemm_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
                    const uint32_t* __restrict__ B_packed, const uint16_t* __restrict__ v,
                    void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype, int m_tiles,
-                   int n_tiles)
+                   int n_tiles, int v_stride, int g_shift)
 {
     constexpr int THREADS = WM * 128;
     constexpr int ROWS = THREADS / 8;    // tile rows covered by one staging pass
@@ -154,6 +154,7 @@ linear_gemm_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ 
     }
     uint32_t vabs_row[WQ];               // row mode: |v| of the thread's W rows, in both halves
     uint32_t vneg_row[WQ];               // row mode: 0xFF if v < 0 (flips every sign bit)
+    const uint16_t* vgrow[WQ];           // grouped mode: the scales of the thread's W rows
 #pragma unroll
     for (int q = 0; q < WQ; ++q) {
         const int row = min(n0 + ld_row + ROWS * q, d_out - 1) - n0;
@@ -165,10 +166,11 @@ linear_gemm_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ 
             vabs_row[q] = aa;
             vneg_row[q] = (h & 0x8000u) ? 0xFFu : 0u;
         }
+        if constexpr (AXIS == 2) vgrow[q] = v + (int64_t)(n0 + row) * v_stride;
     }
 
     uint4v xg[XQ], wg[WQ], vcg;
-    uint32_t sb[WQ];
+    uint32_t sb[WQ], vgq[WQ];            // vgq: grouped mode, the step's scale per W row
     const uint4v zero = {0, 0, 0, 0};
 
     // GUARD: the last, partial step of a d_in that is not a multiple of 64 (it is one of 32).
@@ -184,6 +186,7 @@ linear_gemm_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ 
         for (int q = 0; q < WQ; ++q) {
             wg[q] = col_ok ? *(const uint4v*)(wb + woff[q]) : zero;
             sb[q] = col_ok ? (uint32_t) * (const uint8_t*)(sp + soff[q]) : 0xFFu;
+            if constexpr (AXIS == 2) vgq[q] = col_ok ? (uint32_t)vgrow[q][(kb + ld_c) >> g_shift] : 0u;
         }
         if constexpr (AXIS == 1) vcg = col_ok ? *(const uint4v*)(v + kb + ld_c) : zero;
     };
@@ -199,6 +202,9 @@ linear_gemm_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ 
             if constexpr (AXIS == 0) {
                 const uint32_t aa = vabs_row[q];
                 what = add_signed_scale(w16, ~sb[q] ^ vneg_row[q], (uint4v){aa, aa, aa, aa});
+            } else if constexpr (AXIS == 2) {
+                const uint32_t h = vgq[q], a = h & 0x7FFFu, aa = a | (a << 16);
+                what = add_signed_scale(w16, ~sb[q] ^ ((h & 0x8000u) ? 0xFFu : 0u), (uint4v){aa, aa, aa, aa});
             } else {
                 // per-input scales: fold each scale's own sign into its negate bit
                 uint32_t vsign = 0;
@@ -530,7 +536,7 @@ static int launch_gemm_pipe(const void* X, const void* W_b, const uint32_t* B_pa
 // Requires d_in % 64 == 0.
 struct SmallRegs {
     uint4v xg[2], wg[2], vcg;
-    uint32_t sb[2];
+    uint32_t sb[2], vg[2];               // vg: grouped mode, the step's scale per W row
 };
 
 template <int XDT, int AXIS, int DEPTH>
@@ -538,7 +544,7 @@ __global__ void __launch_bounds__(256, 2)
 linear_gemm_small_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
                          const uint32_t* __restrict__ B_packed, const uint16_t* __restrict__ v,
                          void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype, int m_tiles,
-                         int n_tiles)
+                         int n_tiles, int v_stride, int g_shift)
 {
     constexpr int BM = 64, BN = 64, ROWS = 32, Q = 2;
     constexpr int XS = BM * kGemmLDK, STAGE = (BM + BN) * kGemmLDK;               // halves
@@ -560,6 +566,7 @@ linear_gemm_small_kernel(const uint16_t* __restrict__ X, const uint16_t* __restr
     const char* wbase = (const char*)(W_b + (int64_t)n0 * K);
     const char* sbase = (const char*)B_packed + (((int64_t)n0 * K) >> 3);
     uint32_t xoff[Q], woff[Q], soff[Q], vabs_row[Q], vneg_row[Q];
+    const uint16_t* vgrow[Q];
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
         const int xr = min(m0 + ld_row + ROWS * q, M - 1) - m0;
@@ -573,6 +580,7 @@ linear_gemm_small_kernel(const uint16_t* __restrict__ X, const uint16_t* __restr
             vabs_row[q] = a | (a << 16);
             vneg_row[q] = (h & 0x8000u) ? 0xFFu : 0u;
         }
+        if constexpr (AXIS == 2) vgrow[q] = v + (int64_t)(n0 + wr) * v_stride;
     }
 
     auto load_global = [&](SmallRegs& G, int step) {
@@ -585,6 +593,7 @@ linear_gemm_small_kernel(const uint16_t* __restrict__ X, const uint16_t* __restr
             G.xg[q] = *(const uint4v*)(xb + xoff[q]);
             G.wg[q] = *(const uint4v*)(wb + woff[q]);
             G.sb[q] = (uint32_t) * (const uint8_t*)(sp + soff[q]);
+            if constexpr (AXIS == 2) G.vg[q] = (uint32_t)vgrow[q][(kb + ld_c) >> g_shift];
         }
         if constexpr (AXIS == 1) G.vcg = *(const uint4v*)(v + kb + ld_c);
     };
@@ -597,6 +606,9 @@ linear_gemm_small_kernel(const uint16_t* __restrict__ X, const uint16_t* __restr
             if constexpr (AXIS == 0) {
                 const uint32_t aa = vabs_row[q];
                 what = add_signed_scale(w16, ~G.sb[q] ^ vneg_row[q], (uint4v){aa, aa, aa, aa});
+            } else if constexpr (AXIS == 2) {
+                const uint32_t h = G.vg[q], a = h & 0x7FFFu, aa = a | (a << 16);
+                what = add_signed_scale(w16, ~G.sb[q] ^ ((h & 0x8000u) ? 0xFFu : 0u), (uint4v){aa, aa, aa, aa});
             } else {
                 uint32_t vsign = 0;
 #pragma unroll
@@ -667,7 +679,7 @@ linear_gemm_small_kernel(const uint16_t* __restrict__ X, const uint16_t* __restr
 template <int XDT, int AXIS>
 static int launch_gemm_small(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
                              void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
-                             hipStream_t stream)
+                             hipStream_t stream, int v_stride = 0, int g_shift = 31)
 {
     const int m_tiles = (int)((M + 63) / 64), n_tiles = (int)((d_out + 63) / 64);
     const int n_groups = (n_tiles + kXcds - 1) / kXcds;
@@ -675,14 +687,14 @@ static int launch_gemm_small(const void* X, const void* W_b, const uint32_t* B_p
     // four steps in flight (eight were measured too: 3-10 % slower, they halve the occupancy)
     hipLaunchKernelGGL((linear_gemm_small_kernel<XDT, AXIS, 4>), grid, dim3(256), 0, stream,
                        (const uint16_t*)X, (const uint16_t*)W_b, B_packed, v, Y, (int)M, (int)d_out,
-                       (int)d_in, y_dtype, m_tiles, n_tiles);
+                       (int)d_in, y_dtype, m_tiles, n_tiles, v_stride, g_shift);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 template <int XDT, int AXIS, int BM, int WM>
 static int launch_gemm(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
                        void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
-                       hipStream_t stream)
+                       hipStream_t stream, int v_stride = 0, int g_shift = 31)
 {
     const int m_tiles = (int)((M + BM - 1) / BM);
     const int n_tiles = (int)((d_out + kGemmBN - 1) / kGemmBN);
@@ -690,7 +702,7 @@ static int launch_gemm(const void* X, const void* W_b, const uint32_t* B_packed,
     const dim3 grid((unsigned)((int64_t)n_groups * kXcds * m_tiles));
     hipLaunchKernelGGL((linear_gemm_kernel<XDT, AXIS, BM, WM>), grid, dim3(WM * 128), 0, stream,
                        (const uint16_t*)X, (const uint16_t*)W_b, B_packed, v, Y, (int)M, (int)d_out,
-                       (int)d_in, y_dtype, m_tiles, n_tiles);
+                       (int)d_in, y_dtype, m_tiles, n_tiles, v_stride, g_shift);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -719,6 +731,30 @@ static int launch_gemm_bm(const void* X, const void* W_b, const uint32_t* B_pack
     if (tune_value("gemm_wm", 4) == 4)
         return launch_gemm<XDT, AXIS, 256, 4>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
     return launch_gemm<XDT, AXIS, 256, 2>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
+}
+
+// Blockwise scales: the small-tile kernel for under-filled grids, else the 256 x 128 (or, for
+// short batches, 128 x 128) tile kernel with two workgroups per compute unit.
+template <int XDT>
+static int launch_gemm_group(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v, void* Y,
+                             int64_t M, int64_t d_out, int64_t d_in, int y_dtype, int v_stride, int g_shift,
+                             hipStream_t stream)
+{
+    const int64_t big_tiles = ((M + 255) / 256) * ((d_out + kGemmBN - 1) / kGemmBN);
+    if (d_in % 64 == 0 && big_tiles <= 128)
+        return launch_gemm_small<XDT, 2>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream, v_stride, g_shift);
+    if (M <= 128)
+        return launch_gemm<XDT, 2, 128, 2>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream, v_stride, g_shift);
+    return launch_gemm<XDT, 2, 256, 4>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream, v_stride, g_shift);
+}
+
+int launch_linear_gemm_group(int x_dtype, int y_dtype, const void* X, const void* W_b,
+                             const uint32_t* B_packed, const uint16_t* v, void* Y, int64_t M,
+                             int64_t d_out, int64_t d_in, int v_stride, int g_shift, hipStream_t stream)
+{
+    if (x_dtype == kBF16)
+        return launch_gemm_group<kBF16>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, v_stride, g_shift, stream);
+    return launch_gemm_group<kF16>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, v_stride, g_shift, stream);
 }
 
 int launch_linear_gemm(int x_dtype, int y_dtype, int axis, const void* X, const void* W_b,

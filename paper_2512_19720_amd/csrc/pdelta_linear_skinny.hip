@@ -1,7 +1,11 @@
 // Decode-shaped delta linear layer (M <= 64 tokens):
 //   row:  Y[m,o] = sum_i X[m,i] W_b[o,i] + v[o] * sum_i X[m,i] B[o,i]
 //   col:  Y[m,o] = sum_i X[m,i] W_b[o,i] +        sum_i (X[m,i] v[i]) B[o,i]
-// (paper Eq. 1 applied inside the layer forward, never forming W_hat in memory).
+//   grouped (AXIS 2): Y[m,o] = sum_i X[m,i] W_b[o,i] + sum_i X[m,i] (v[o, i / g] B[o,i])
+//         with v[row * v_stride + (i >> g_shift)]; v_stride = 0 shares the scales between rows
+//         (one scalar for the whole matrix when the group is all of d_in)
+// (paper Eq. 1 applied inside the layer forward, never forming W_hat in memory; the grouped form
+// is the blockwise extension the paper's conclusion names, its scalar case the BitDelta baseline).
 //
 // The layer is HBM-bound: every weight (2 B) and every sign bit (1/8 B) is read exactly once
 // and nothing else of size is touched.  The arithmetic rides on the matrix cores, which are
@@ -64,18 +68,37 @@ __device__ __forceinline__ uint4v scale_x(uint4v x, uint4v v) {
     return r;
 }
 
+// Grouped scales: the sign-part operands are fp16 whatever the dtype of X: A = fp16(X) and
+// B = +-v (the exact product of the +-1 pattern and the group's scale).
+template <int XDT>
+__device__ __forceinline__ uint4v x_as_f16(uint4v x) {
+    if constexpr (XDT == kF16) return x;
+    else return scale_x<XDT>(x, (uint4v){0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u});
+}
+__device__ __forceinline__ uint4v signs_times_scale(uint4v pm, uint32_t v_half) {
+    const uint32_t vv = v_half | (v_half << 16);
+    uint4v r;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t sp = pm[p];
+        r[p] = as_u32(as_half2(sp) * as_half2(vv));                              // v_pk_mul_f16, exact
+    }
+    return r;
+}
+
 template <int MT, int AXIS>
 struct SkinnyStep {
     uint4v w[4];        // W_b operand, one per 32-input block
     uint4v sw;          // the step's four sign words of this lane's row
     uint4v x[MT][4];    // X operand per 16-token tile
     uint4v vc[4];       // v_col (column mode only)
+    uint32_t vg[4];     // grouped mode: the scale of this lane's row for each 32-input block
 };
 
 template <int MT, int AXIS, bool K128>
 __device__ __forceinline__ void skinny_load(SkinnyStep<MT, AXIS>& r, const uint16_t* wrow,
                                             const uint32_t* brow, const uint16_t* const (&xrow)[MT],
-                                            const uint16_t* vcol, int kb, int K)
+                                            const uint16_t* vcol, int kb, int K, int g_shift = 31)
 {
     const uint4v zero = {0, 0, 0, 0};
     if constexpr (K128) {
@@ -93,6 +116,7 @@ __device__ __forceinline__ void skinny_load(SkinnyStep<MT, AXIS>& r, const uint1
         for (int mt = 0; mt < MT; ++mt)
             r.x[mt][j] = live ? *(const uint4v*)(xrow[mt] + k) : zero;
         if constexpr (AXIS == 1) r.vc[j] = live ? *(const uint4v*)(vcol + k) : zero;
+        if constexpr (AXIS == 2) r.vg[j] = live ? (uint32_t)vcol[k >> g_shift] : 0u;   // vcol: this row's scales
     }
 }
 
@@ -125,12 +149,19 @@ __device__ __forceinline__ void skinny_compute(const SkinnyStep<MT, AXIS>& r, in
                 accb[mt] = mfma16<XDT>(xj[mt], wj, accb[mt]);
                 accs[mt] = mfma16<XDT>(xj[mt], s, accs[mt]);
             }
-        } else {
+        } else if constexpr (AXIS == 1) {
             const uint4v s = expand_signs<kF16>(byte);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 accb[mt] = mfma16<XDT>(xj[mt], wj, accb[mt]);
                 accs[mt] = mfma16<kF16>(scale_x<XDT>(xj[mt], r.vc[j]), s, accs[mt]);
+            }
+        } else {
+            const uint4v s = signs_times_scale(expand_signs<kF16>(byte), r.vg[j]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                accb[mt] = mfma16<XDT>(xj[mt], wj, accb[mt]);
+                accs[mt] = mfma16<kF16>(x_as_f16<XDT>(xj[mt]), s, accs[mt]);
             }
         }
     }
@@ -142,7 +173,7 @@ template <int XDT, int AXIS, int MT, int WAVES, int DEPTH, bool K128>
 __global__ void __launch_bounds__(WAVES * 64)
 linear_skinny_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
                      const uint32_t* __restrict__ B_packed, const uint16_t* __restrict__ v,
-                     void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype)
+                     void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype, int v_stride, int g_shift)
 {
     extern __shared__ float red[];                    // [WAVES][MT][4][64]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -155,7 +186,7 @@ linear_skinny_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict_
     const int perm = (n * 4 + g) * 4;
     const uint16_t* wrow = W_b + (int64_t)min(n0 + ln, d_out - 1) * K + lg * 8;
     const uint32_t* brow = B_packed + (int64_t)o * (K >> 5);
-    const uint16_t* vcol = AXIS == 1 ? v + g * 8 : nullptr;
+    const uint16_t* vcol = AXIS == 1 ? v + g * 8 : (AXIS == 2 ? v + (int64_t)o * v_stride : nullptr);
     const uint16_t* xrow[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -186,27 +217,27 @@ linear_skinny_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict_
     auto kb_of = [&](int i) { return (wave + i * WAVES) << 7; };
     if (mine >= DEPTH) {
 #pragma unroll
-        for (int d = 0; d < DEPTH; ++d) skinny_load<MT, AXIS, K128>(buf[d], wrow, brow, xrow, vcol, kb_of(d), K);
+        for (int d = 0; d < DEPTH; ++d) skinny_load<MT, AXIS, K128>(buf[d], wrow, brow, xrow, vcol, kb_of(d), K, g_shift);
         int i = 0;
         for (; i + 2 * DEPTH <= mine; i += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
                 skinny_compute<XDT, MT, AXIS>(buf[d], g, perm, accb, accs);
-                skinny_load<MT, AXIS, K128>(buf[d], wrow, brow, xrow, vcol, kb_of(i + DEPTH + d), K);
+                skinny_load<MT, AXIS, K128>(buf[d], wrow, brow, xrow, vcol, kb_of(i + DEPTH + d), K, g_shift);
             }
         }
         const int rest = mine - i - DEPTH;            // loads still to issue, 0 <= rest < DEPTH
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             skinny_compute<XDT, MT, AXIS>(buf[d], g, perm, accb, accs);
-            if (d < rest) skinny_load<MT, AXIS, K128>(buf[d], wrow, brow, xrow, vcol, kb_of(i + DEPTH + d), K);
+            if (d < rest) skinny_load<MT, AXIS, K128>(buf[d], wrow, brow, xrow, vcol, kb_of(i + DEPTH + d), K, g_shift);
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
             if (d < rest) skinny_compute<XDT, MT, AXIS>(buf[d], g, perm, accb, accs);
     } else {
         for (int i = 0; i < mine; ++i) {              // fewer steps than the ring is deep
-            skinny_load<MT, AXIS, K128>(buf[0], wrow, brow, xrow, vcol, kb_of(i), K);
+            skinny_load<MT, AXIS, K128>(buf[0], wrow, brow, xrow, vcol, kb_of(i), K, g_shift);
             skinny_compute<XDT, MT, AXIS>(buf[0], g, perm, accb, accs);
         }
     }
@@ -255,7 +286,8 @@ template <int XDT, int AXIS, int WAVES, int DEPTH, bool STAGE_X>
 __device__ __forceinline__ void
 staged_body(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
             const uint32_t* __restrict__ B_packed, const uint16_t* __restrict__ v,
-            void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype, int block)
+            void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype, int block,
+            int v_stride = 0, int g_shift = 31)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // nibble -> four +-1.0 values (of the sign operand's dtype): two conflict-free 8-byte LDS
@@ -268,7 +300,11 @@ staged_body(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
     float* red = (float*)smem;                                        // [WAVES][4][64]
     uint32_t* s_sign = (uint32_t*)(smem + WAVES * 1024);              // [16][spr]
     uint16_t* s_x = (uint16_t*)(s_sign + 16 * spr);                   // [M][xpr]      (STAGE_X)
-    uint16_t* s_xv = s_x + (STAGE_X ? M * xpr : 0);                   // [M][xpr]      (STAGE_X, col)
+    uint16_t* s_xv = s_x + (STAGE_X ? M * xpr : 0);                   // [M][xpr]      (STAGE_X: col, or grouped with bf16 X)
+    // grouped mode: the scales of the workgroup's 16 rows, [16][ngrp] fp16, behind the X copies
+    constexpr bool XV = STAGE_X && (AXIS == 1 || (AXIS == 2 && XDT == kBF16));
+    const int ngrp = g_shift >= 31 ? 1 : (K >> g_shift);
+    uint16_t* s_v = s_xv + (XV ? M * xpr : 0);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -346,6 +382,14 @@ staged_body(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
                 *(uint4v*)(s_x + t * xpr + u * 8) = xv;
                 if constexpr (AXIS == 1)
                     *(uint4v*)(s_xv + t * xpr + u * 8) = scale_x<XDT>(xv, *(const uint4v*)(v + u * 8));
+                if constexpr (AXIS == 2 && XDT == kBF16)
+                    *(uint4v*)(s_xv + t * xpr + u * 8) = x_as_f16<XDT>(xv);
+            }
+        }
+        if constexpr (AXIS == 2) {
+            for (int i = tid; i < 16 * ngrp; i += WAVES * 64) {
+                const int row = i / ngrp, c = i - row * ngrp;
+                s_v[i] = v[(int64_t)min(n0 + row, d_out - 1) * v_stride + c];
             }
         }
     }
@@ -355,6 +399,7 @@ staged_body(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
     const uint32_t* my_sign = s_sign + n * spr;
     const uint16_t* my_x = s_x + tok * xpr + g * 8;
     const uint16_t* my_xv = s_xv + tok * xpr + g * 8;
+    const uint16_t* my_v = s_v + n * ngrp;
 
     auto compute = [&](const StagedStep<AXIS, STAGE_X>& r, int kb) {
         const uint4v sw = *(const uint4v*)(my_sign + (kb >> 5));
@@ -364,10 +409,12 @@ staged_body(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
             uint4v xa, xs;
             if constexpr (STAGE_X) {
                 xa = *(const uint4v*)(my_x + kb + j * 32);
-                if constexpr (AXIS == 1) xs = *(const uint4v*)(my_xv + kb + j * 32);
+                if constexpr (XV) xs = *(const uint4v*)(my_xv + kb + j * 32);
+                else if constexpr (AXIS == 2) xs = xa;
             } else {
                 xa = to_mfma_layout(r.x[j]);
                 if constexpr (AXIS == 1) xs = scale_x<XDT>(xa, r.vc[j]);
+                if constexpr (AXIS == 2) xs = x_as_f16<XDT>(xa);
             }
             const uint4v wj = to_mfma_layout(r.w[j]);
             uint4v sg;
@@ -380,6 +427,7 @@ staged_body(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
             } else {
                 sg = expand_signs<(AXIS == 0 ? XDT : kF16)>(byte);
             }
+            if constexpr (AXIS == 2) sg = signs_times_scale(sg, my_v[(kb + j * 32) >> g_shift]);
             accb = mfma16<XDT>(xa, wj, accb);
             if constexpr (AXIS == 0) accs = mfma16<XDT>(xa, sg, accs);
             else accs = mfma16<kF16>(xs, sg, accs);
@@ -434,10 +482,11 @@ template <int XDT, int AXIS, int WAVES, int DEPTH, bool STAGE_X>
 __global__ void __launch_bounds__(WAVES * 64)
 linear_skinny_staged_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
                             const uint32_t* __restrict__ B_packed, const uint16_t* __restrict__ v,
-                            void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype)
+                            void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype, int v_stride,
+                            int g_shift)
 {
     staged_body<XDT, AXIS, WAVES, DEPTH, STAGE_X>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype,
-                                                  (int)blockIdx.x);
+                                                  (int)blockIdx.x, v_stride, g_shift);
 }
 
 // Many layers in one launch (all with the same batch M and dtypes; shapes and axis per layer).
@@ -467,17 +516,20 @@ linear_skinny_batch_kernel(const pdelta_layer* __restrict__ layers, int n_layers
 constexpr size_t kStagedLdsLimit = 96 * 1024;
 
 // LDS bytes of the staged kernel, or 0 when the slabs do not fit.
-static size_t staged_lds_bytes(int waves, int axis, bool stage_x, int64_t M, int64_t K)
+// `x_copies`: LDS copies of X (2 when the sign part needs its own fp16 operand: column mode, or
+// grouped mode with bf16 X); `scale_halves`: grouped mode's 16 rows of scales.
+static size_t staged_lds_bytes(int waves, int x_copies, bool stage_x, int64_t M, int64_t K, int64_t scale_halves = 0)
 {
-    size_t bytes = (size_t)waves * 1024 + (size_t)16 * (K / 32 + 4) * 4;
-    if (stage_x) bytes += (size_t)M * (K + 8) * 2 * (axis == 1 ? 2 : 1);
+    size_t bytes = (size_t)waves * 1024 + (size_t)16 * (K / 32 + 4) * 4 + (size_t)scale_halves * 2 + 16;
+    if (stage_x) bytes += (size_t)M * (K + 8) * 2 * x_copies;
     return bytes <= kStagedLdsLimit ? bytes : 0;
 }
+static int x_copies_of(int axis, int x_dtype) { return axis == 1 || (axis == 2 && x_dtype == kBF16) ? 2 : 1; }
 
 template <int XDT, int AXIS, int WAVES, int DEPTH, bool STAGE_X>
 static int launch_staged(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
                          void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype, size_t lds,
-                         hipStream_t stream)
+                         hipStream_t stream, int v_stride = 0, int g_shift = 31)
 {
     const dim3 grid((unsigned)((d_out + 15) / 16));
     auto kernel = linear_skinny_staged_kernel<XDT, AXIS, WAVES, DEPTH, STAGE_X>;
@@ -485,7 +537,8 @@ static int launch_staged(const void* X, const void* W_b, const uint32_t* B_packe
     if (lds > 48 * 1024 && opt_in_dynamic_lds((const void*)kernel, (int)kStagedLdsLimit, &lds_opted_in) != 0)
         return -1;           // above the default dynamic-LDS limit the kernel has to opt in (once)
     hipLaunchKernelGGL(kernel, grid, dim3(WAVES * 64), lds, stream, (const uint16_t*)X,
-                       (const uint16_t*)W_b, B_packed, v, Y, (int)M, (int)d_out, (int)d_in, y_dtype);
+                       (const uint16_t*)W_b, B_packed, v, Y, (int)M, (int)d_out, (int)d_in, y_dtype, v_stride,
+                       g_shift);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -502,12 +555,13 @@ static int try_staged(const void* X, const void* W_b, const uint32_t* B_packed, 
     // (not in column mode with X read through L2: that variant needs more than the 128 registers
     // a 16-wave workgroup leaves per lane and spills - measured 37 us against 24 us with 8 waves)
     const bool x_small = M * d_in <= 24576;
-    const bool col16_ok = x_small && staged_lds_bytes(16, AXIS, true, M, d_in) != 0;   // X fits LDS at 16 waves
+    constexpr int XC = AXIS == 1 ? 2 : 1;             // LDS copies of X
+    const bool col16_ok = x_small && staged_lds_bytes(16, XC, true, M, d_in) != 0;   // X fits LDS at 16 waves
     const int waves = tune_value("stg_waves", wide_few && (AXIS == 0 || col16_ok) ? 16 : 8);
     const bool want_x = tune_value("stg_x", 1) != 0;
-    size_t lds = want_x ? staged_lds_bytes(waves, AXIS, true, M, d_in) : 0;
+    size_t lds = want_x ? staged_lds_bytes(waves, XC, true, M, d_in) : 0;
     const bool stage_x = lds != 0 && x_small;
-    if (!stage_x) lds = staged_lds_bytes(waves, AXIS, false, M, d_in);
+    if (!stage_x) lds = staged_lds_bytes(waves, XC, false, M, d_in);
     // Row mode, small batch, exactly four steps per wave (d_in = 4096 at 8 waves): all four in
     // flight from the start is 3 % faster than a ring of two (same-run A/B); elsewhere it makes no
     // difference or loses (column mode and larger batches carry more registers per step).
@@ -532,13 +586,13 @@ static int try_staged(const void* X, const void* W_b, const uint32_t* B_packed, 
 template <int XDT, int AXIS, int MT, int WAVES, int DEPTH, bool K128>
 static int launch_one(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
                       void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
-                      hipStream_t stream)
+                      hipStream_t stream, int v_stride = 0, int g_shift = 31)
 {
     const dim3 grid((unsigned)((d_out + 15) / 16));
     const size_t lds = (size_t)WAVES * MT * 256 * sizeof(float);
     hipLaunchKernelGGL((linear_skinny_kernel<XDT, AXIS, MT, WAVES, DEPTH, K128>), grid, dim3(WAVES * 64), lds,
                        stream, (const uint16_t*)X, (const uint16_t*)W_b, B_packed, v, Y, (int)M,
-                       (int)d_out, (int)d_in, y_dtype);
+                       (int)d_out, (int)d_in, y_dtype, v_stride, g_shift);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -580,13 +634,13 @@ int launch_linear_skinny_batch(int x_dtype, int y_dtype, const pdelta_layer* lay
     for (int l = 0; l < n_layers; ++l) {
         const pdelta_layer& L = layers_host[l];
         if (L.d_in % 128 != 0) return 1;
-        if (M * L.d_in > 24576 || staged_lds_bytes(8, L.axis, true, M, L.d_in) == 0) stage_x = false;
+        if (M * L.d_in > 24576 || staged_lds_bytes(8, L.axis == 1 ? 2 : 1, true, M, L.d_in) == 0) stage_x = false;
     }
     int64_t total = 0;
     size_t lds = 0;
     for (int l = 0; l < n_layers; ++l) {
         const pdelta_layer& L = layers_host[l];
-        const size_t need = staged_lds_bytes(8, L.axis, stage_x, M, L.d_in);
+        const size_t need = staged_lds_bytes(8, L.axis == 1 ? 2 : 1, stage_x, M, L.d_in);
         if (need == 0) return 1;
         if (need > lds) lds = need;
         total += (L.d_out + 15) / 16;
@@ -601,6 +655,47 @@ int launch_linear_skinny_batch(int x_dtype, int y_dtype, const pdelta_layer* lay
     hipLaunchKernelGGL(kernel, dim3((unsigned)total), dim3(8 * 64), lds, stream, layers_device,
                        n_layers, (int)M, y_dtype);
     return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Grouped (blockwise / scalar) scales, M <= kSkinnyMaxM: the staged kernel when it applies (up to
+// 16 tokens, d_in a multiple of 128, slabs fit LDS), else the plain kernel.
+template <int XDT>
+static int launch_group(int y_dtype, const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
+                        void* Y, int64_t M, int64_t d_out, int64_t d_in, int v_stride, int g_shift,
+                        hipStream_t stream)
+{
+    if (M <= 16 && d_in % 128 == 0 && tune_value("skinny_staged", 1) != 0) {
+        const int64_t scale_halves = 16 * (g_shift >= 31 ? 1 : (d_in >> g_shift));
+        const int xc = x_copies_of(2, XDT);
+        size_t lds = M * d_in <= 24576 ? staged_lds_bytes(8, xc, true, M, d_in, scale_halves) : 0;
+        const bool stage_x = lds != 0;
+        if (!stage_x) lds = staged_lds_bytes(8, xc, false, M, d_in, scale_halves);
+        if (lds != 0)
+            return stage_x ? launch_staged<XDT, 2, 8, 2, true>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, lds,
+                                                               stream, v_stride, g_shift)
+                           : launch_staged<XDT, 2, 8, 2, false>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, lds,
+                                                                stream, v_stride, g_shift);
+    }
+#define PDELTA_GO(MT, DEPTH)                                                                                   \
+    return d_in % 128 == 0                                                                                     \
+               ? launch_one<XDT, 2, MT, 8, DEPTH, true>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream, \
+                                                        v_stride, g_shift)                                     \
+               : launch_one<XDT, 2, MT, 8, DEPTH, false>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream, \
+                                                         v_stride, g_shift)
+    if (M <= 16) PDELTA_GO(1, 2);
+    if (M <= 32) PDELTA_GO(2, 2);
+    if (M <= 48) PDELTA_GO(3, 1);
+    PDELTA_GO(4, 1);
+#undef PDELTA_GO
+}
+
+int launch_linear_skinny_group(int x_dtype, int y_dtype, const void* X, const void* W_b,
+                               const uint32_t* B_packed, const uint16_t* v, void* Y, int64_t M,
+                               int64_t d_out, int64_t d_in, int v_stride, int g_shift, hipStream_t stream)
+{
+    if (x_dtype == kBF16)
+        return launch_group<kBF16>(y_dtype, X, W_b, B_packed, v, Y, M, d_out, d_in, v_stride, g_shift, stream);
+    return launch_group<kF16>(y_dtype, X, W_b, B_packed, v, Y, M, d_out, d_in, v_stride, g_shift, stream);
 }
 
 int launch_linear_skinny(int x_dtype, int y_dtype, int axis, const void* X, const void* W_b,

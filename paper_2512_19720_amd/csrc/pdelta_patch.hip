@@ -80,10 +80,13 @@ __device__ __forceinline__ void round_sums(const float (&wf)[ROWS][8], const flo
 // Patches rows row0 .. row0 + ROWS*GROUPS - 1 at columns col .. col + 7.  Loads are
 // unconditional, ROWS rows at a time (row indices clamped into the matrix; stores of clamped
 // rows are skipped), so that they are all in flight together.
+// AXIS 2: blockwise scales v[row * v_stride + (col >> g_shift)] (groups are multiples of 8 inputs,
+// so the eight weights of a thread share one scale).
 template <int DT, int AXIS, int ROWS, int GROUPS>
 __device__ __forceinline__ void
 patch_column_strip(const uint16_t* W_b, const uint8_t* __restrict__ B_bytes,
-                   const uint16_t* __restrict__ v, uint16_t* W_out, int d_out, int d_in, int row0, int col)
+                   const uint16_t* __restrict__ v, uint16_t* W_out, int d_out, int d_in, int row0, int col,
+                   int v_stride = 0, int g_shift = 31)
 {
     float vc[8];
     if constexpr (AXIS == 1) {
@@ -104,7 +107,9 @@ patch_column_strip(const uint16_t* W_b, const uint8_t* __restrict__ B_bytes,
             const int64_t off = (int64_t)row * d_in + col;
             w[r] = *(const uint4v*)(W_b + off);
             byte[r] = B_bytes[off >> 3];
-            vr[r] = AXIS == 0 ? f16_bits_to_f32(v[row]) : 0.0f;
+            vr[r] = AXIS == 0   ? f16_bits_to_f32(v[row])
+                    : AXIS == 2 ? f16_bits_to_f32(v[(int64_t)row * v_stride + (col >> g_shift)])
+                                : 0.0f;
         }
         uint4v out[ROWS];
 #pragma unroll
@@ -115,7 +120,7 @@ patch_column_strip(const uint16_t* W_b, const uint8_t* __restrict__ B_bytes,
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     wf[k][e] = bits_to_f32<DT>((w[r2 + k][e >> 1] >> ((e & 1) * 16)) & 0xFFFFu);
-                    const float scale = AXIS == 0 ? vr[r2 + k] : vc[e];
+                    const float scale = AXIS == 1 ? vc[e] : vr[r2 + k];
                     // bit 1 -> +scale, bit 0 -> -scale: flip the sign where the sign bit is clear
                     const uint32_t flip = (~byte[r2 + k] << (31 - e)) & 0x80000000u;
                     sf[k][e] = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, scale) ^ flip);
@@ -138,13 +143,14 @@ patch_column_strip(const uint16_t* W_b, const uint8_t* __restrict__ B_bytes,
 template <int DT, int AXIS>
 __global__ void __launch_bounds__(kPatchThreads)
 patch_kernel(const uint16_t* W_b, const uint8_t* __restrict__ B_bytes,
-             const uint16_t* __restrict__ v, uint16_t* W_out, int d_out, int d_in, int n_seg)
+             const uint16_t* __restrict__ v, uint16_t* W_out, int d_out, int d_in, int n_seg,
+             int v_stride, int g_shift)
 {
     const int seg = (int)blockIdx.x % n_seg, row_block = (int)blockIdx.x / n_seg;
     const int col = (seg * kPatchThreads + threadIdx.x) * 8;
     if (col >= d_in) return;
     patch_column_strip<DT, AXIS, 4, kPatchRows / 4>(W_b, B_bytes, v, W_out, d_out, d_in,
-                                                    row_block * kPatchRows, col);
+                                                    row_block * kPatchRows, col, v_stride, g_shift);
 }
 
 // Batched merge: workgroup b patches 16 consecutive rows (all columns) of the last layer whose
@@ -188,14 +194,23 @@ int launch_patch_batch(int w_dtype, const pdelta_layer* layers_host, const pdelt
 
 template <int DT, int AXIS>
 static int launch_patch(const void* W_b, const uint32_t* B_packed, const uint16_t* v, void* W_out,
-                        int64_t d_out, int64_t d_in, hipStream_t stream)
+                        int64_t d_out, int64_t d_in, hipStream_t stream, int v_stride = 0, int g_shift = 31)
 {
     const int64_t n_seg = (d_in / 8 + kPatchThreads - 1) / kPatchThreads;
     const int64_t n_blocks = (d_out + kPatchRows - 1) / kPatchRows;          // <= 2^19 x 2^11
     hipLaunchKernelGGL((patch_kernel<DT, AXIS>), dim3((unsigned)(n_blocks * n_seg)), dim3(kPatchThreads), 0,
                        stream, (const uint16_t*)W_b, (const uint8_t*)B_packed, v, (uint16_t*)W_out,
-                       (int)d_out, (int)d_in, (int)n_seg);
+                       (int)d_out, (int)d_in, (int)n_seg, v_stride, g_shift);
     return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_patch_group(int w_dtype, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
+                       void* W_out, int64_t d_out, int64_t d_in, int v_stride, int g_shift,
+                       hipStream_t stream)
+{
+    if (w_dtype == kBF16)
+        return launch_patch<kBF16, 2>(W_b, B_packed, v, W_out, d_out, d_in, stream, v_stride, g_shift);
+    return launch_patch<kF16, 2>(W_b, B_packed, v, W_out, d_out, d_in, stream, v_stride, g_shift);
 }
 
 int launch_patch_dispatch(int w_dtype, int axis, const void* W_b, const uint32_t* B_packed,

@@ -265,6 +265,51 @@ def test_linear_variants_argument_errors():
     assert run(variants(axis=pd.COL), axis=pd.PER_REQUEST, Y=A + 0x3010000 + 128, d_out=64, d_in=128) == pd.EINVAL
 
 
+def test_group_scale_entry_points_argument_errors():
+    L = pd.lib()
+    W, Bp, v, X, Y, ws = A, A + (1 << 32), A + (2 << 32), A + (3 << 32), A + (4 << 32), A + (5 << 32)
+
+    def lin(X=X, W=W, B=Bp, v=v, group=32, shared=0, Y=Y, M=4, d_out=64, d_in=128, xdt=pd.F16, ydt=pd.F16):
+        return L.pdelta_linear_group(X, W, B, v, group, shared, Y, M, d_out, d_in, xdt, ydt, None)
+
+    for null in ("X", "W", "B", "v", "Y"):
+        assert lin(**{null: None}) == pd.EINVAL
+    assert lin(M=-1) == pd.EINVAL and lin(group=0) == pd.EINVAL and lin(shared=2) == pd.EINVAL
+    for bad_group in (16, 48, 96, 256):                                # too small, not a power of two, does not divide
+        assert lin(group=bad_group) == pd.ESHAPE
+    assert lin(d_in=100, group=100) == pd.ESHAPE                        # d_in itself must be a multiple of 32
+    assert lin(xdt=pd.F32) == pd.EDTYPE and lin(ydt=9) == pd.EDTYPE
+    assert lin(v=v + 2) == pd.EALIGN
+    assert lin(M=0) == pd.OK and lin(M=0, X=None, Y=None) == pd.OK
+    assert lin(M=0, d_in=96, group=96) == pd.OK                         # the whole row is always a valid group
+    assert lin(Y=v) == pd.EINVAL                                        # Y on top of the scales
+    # v has d_out * d_in / group = 256 entries here (512 bytes): a Y that starts inside them overlaps
+    assert lin(Y=v + 64, M=0) == pd.OK                                  # an empty batch writes nothing
+    assert lin(Y=v + 496) == pd.EINVAL
+
+    def patch(W=W, B=Bp, v=v, group=64, shared=0, out=Y, d_out=64, d_in=128, dt=pd.F16):
+        return L.pdelta_patch_group(W, B, v, group, shared, out, d_out, d_in, dt, None)
+
+    for null in ("W", "B", "v", "out"):
+        assert patch(**{null: None}) == pd.EINVAL
+    assert patch(group=24) == pd.ESHAPE and patch(shared=-1) == pd.EINVAL and patch(dt=pd.F32) == pd.EDTYPE
+    assert patch(out=W + 64) == pd.EINVAL and patch(out=Bp) == pd.EINVAL and patch(out=Y + 4) == pd.EALIGN
+
+    def pack(Wf=X, Wb=W, d_out=64, d_in=128, dt=pd.F16, group=32, shared=0, B=Bp, v=v, ws=ws, wsb=1 << 20):
+        return L.pdelta_pack_group(Wf, Wb, d_out, d_in, dt, group, shared, B, v, ws, wsb, None)
+
+    for null in ("Wf", "Wb", "B", "v"):
+        assert pack(**{null: None}) == pd.EINVAL
+    assert pack(group=12) == pd.ESHAPE and pack(dt=5) == pd.EDTYPE and pack(B=Bp + 8) == pd.EALIGN
+    assert L.pdelta_pack_group_workspace_bytes(64, 128, 32, 0) == 0
+    assert L.pdelta_pack_group_workspace_bytes(64, 128, 32, 1) == 8 * 64 * 4
+    assert L.pdelta_pack_group_workspace_bytes(64, 128, 128, 1) == 8 * 64
+    assert L.pdelta_pack_group_workspace_bytes(64, 128, 48, 1) == 0       # invalid group
+    assert pack(shared=1, ws=None) == pd.EWORKSPACE and pack(shared=1, wsb=8 * 64 * 4 - 1) == pd.EWORKSPACE
+    assert pack(shared=1, ws=ws + 8) == pd.EALIGN
+    assert pack(v=X + 64) == pd.EINVAL and pack(B=W) == pd.EINVAL and pack(shared=1, ws=Bp) == pd.EINVAL
+
+
 def test_grad_v_workspace_and_argument_errors():
     L = pd.lib()
     # row: one fp32 partial per (256-token tile, output); col: the same per input, rounded up
