@@ -13,12 +13,21 @@ def pytest_addoption(parser):
                           "(used only by tests/test_oracle_mutations.py for its child runs)")
 
 
+    parser.addoption("--pdelta-lib", default=None,
+                     help="load the C-ABI library from this path instead of the in-tree libpdelta.so "
+                          "(used only by tests/test_sanitizers.py for its child run of the host-side tests)")
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
     path = config.getoption("--oracle-lib")
     if path:
         from oracle import pdelta_oracle
         pdelta_oracle.use_library(path)
+    path = config.getoption("--pdelta-lib")
+    if path:
+        from paper_2512_19720_amd import binding
+        binding._LIB_PATH = path
 
 
 def pytest_sessionstart(session):
