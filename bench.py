@@ -37,6 +37,24 @@ def decode_bytes(d_out: int, d_in: int, M: int, axis: str) -> int:
     return 2 * d_out * d_in + d_out * d_in // 8 + 2 * v_len + 2 * M * d_in + 2 * M * d_out
 
 
+def smi_info() -> dict:
+    """Clocks and partition modes as rocm-smi reports them (a child process; null when unavailable)."""
+    import re
+    import subprocess
+    out = {"sclk_MHz": None, "mclk_MHz": None, "compute_partition": None, "memory_partition": None}
+    try:
+        txt = subprocess.run(["rocm-smi", "--showclocks", "--showcomputepartition", "--showmemorypartition"],
+                             capture_output=True, text=True, timeout=30).stdout
+        for key, pat in (("sclk_MHz", r"sclk clock level:\s*\d+:?\s*\(?(\d+)Mhz"), ("mclk_MHz", r"mclk clock level:\s*\d+:?\s*\(?(\d+)Mhz"),
+                         ("compute_partition", r"Compute Partition:\s*(\S+)"), ("memory_partition", r"Memory Partition:\s*(\S+)")):
+            m = re.search(pat, txt, flags=re.I)
+            if m:
+                out[key] = int(m.group(1)) if key.endswith("MHz") else m.group(1)
+    except Exception as exc:                                   # the figures are informative only
+        out["note"] = f"rocm-smi not usable: {str(exc)[:80]}"
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -44,6 +62,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--skip", type=str, default="")
     ap.add_argument("--sets", type=int, default=24, help="rotating buffer sets for the decode layer")
+    ap.add_argument("--repeats", type=int, default=7, help="timed replays of the K-step graph (median reported)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB) so that "
                          "a rocprofv3 --pmc run of this command has a kernel of known traffic in it")
@@ -140,9 +159,12 @@ def main() -> int:
     rot[0] = 0
     g_steps = graph_of(decode_step, args.steps)            # exactly K steps, rotating buffer sets
     timed(g_steps.replay, 1)
+    # the timed region: `repeats` replays of the K-step graph, each between its own pair of events
+    # (sync, K steps, sync); the median replay is the reported one, min and max show the spread
     t_wall0 = time.perf_counter()
-    ms_total = timed(g_steps.replay, 1)                    # the timed region: sync, K steps, sync
+    replays_ms = sorted(timed(g_steps.replay, 1) for _ in range(max(args.repeats, 1)))
     wall_s = time.perf_counter() - t_wall0
+    ms_total = replays_ms[len(replays_ms) // 2]
     ms_per_step = ms_total / args.steps
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
@@ -150,7 +172,7 @@ def main() -> int:
     for axis, M in cases:
         g_case = graph_of(lambda: decode_call(axis, M), 200)
         timed(g_case.replay, 1)
-        ms = timed(g_case.replay, 1) / 200
+        ms = sorted(timed(g_case.replay, 1) for _ in range(5))[2] / 200      # >= 100 calls, median of 5
         b = decode_bytes(N, K, M, axis)
         per_case[f"{axis}_M{M}"] = {"us": round(ms * 1e3, 3), "GB/s": round(b / ms / 1e6, 1),
                                     "frac_hbm": round(b / ms / 1e6 / HBM_PEAK_GBS, 4)}
@@ -163,35 +185,70 @@ def main() -> int:
 
     # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by the
     # plain-copy calibration); taken from the committed summary when it exists.
-    traffic = None
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "decode_4096x4096_pmc_traffic.md")
     if os.path.exists(tpath):
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = int(float(line.split(":", 1)[1].split()[0]))
+                traffic_source = ("counter figure, not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                                  "of this same command, committed as profiles/decode_4096x4096_pmc_traffic.md")
     launches = args.steps * len(cases)
     avg_launch_us = ms_total * 1e3 / launches
     roofline = {"bound": "hbm", "kernel": "linear_skinny_staged_kernel (decode, 4096x4096 fp16)",
                 "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(value / HBM_PEAK_GBS, 4),
                 "bytes_per_launch": step_bytes // len(cases),
-                "avg_launch_us": round(avg_launch_us, 3), "traffic": traffic}
+                "avg_launch_us": round(avg_launch_us, 3), "traffic": traffic, "traffic_source": traffic_source}
 
-    # what the box is, and what a plain streaming kernel reaches on it ("% of achievable")
+    # what the box is, and what plain kernels reach on it ("% of achievable" next to "% of peak")
     props = torch.cuda.get_device_properties(0)
     device_info = {"name": props.name, "arch": getattr(props, "gcnArchName", ""),
                    "compute_units": props.multi_processor_count,
-                   "clock_MHz": round(getattr(props, "clock_rate", 0) / 1e3) if hasattr(props, "clock_rate") else None,
                    "memory_GiB": round(props.total_memory / 2 ** 30, 1)}
-    csrc = torch.ones(1 << 29, dtype=f16, device=dev)                   # 1 GiB
+    device_info.update(smi_info())
+    sink = torch.zeros(64, dtype=torch.uint8, device=dev)
+    big = torch.empty(1 << 32, dtype=torch.uint8, device=dev)            # 4 GiB, read-only stream
+    big.view(torch.int32).fill_(0x01020304)
+    timed(lambda: pd.pdelta_probe_read_stream(big, sink), 2)
+    rms = sorted(timed(lambda: pd.pdelta_probe_read_stream(big, sink), 3) / 3 for _ in range(3))[1]
+    # the same read-only kernel on pieces of the decode layer's size (35.7 MB per launch, 24 distinct
+    # pieces): what a launch of that size can reach at best, ramp-up and drain included
+    piece = step_bytes // len(cases) // 256 * 256
+    pieces = [big[i * piece:(i + 1) * piece] for i in range(24)]
+    prot = [0]
+
+    def piece_read():
+        pd.pdelta_probe_read_stream(pieces[prot[0] % 24], sink)
+        prot[0] += 1
+
+    g_piece = graph_of(piece_read, 200)
+    timed(g_piece.replay, 1)
+    pms = sorted(timed(g_piece.replay, 1) for _ in range(5))[2] / 200
+    del g_piece, pieces
+    csrc = big[:1 << 30].view(f16)                                       # 1 GiB
     cdst = torch.empty_like(csrc)
     timed(lambda: torch.mul(csrc, 1.0, out=cdst), 3)
     cms = timed(lambda: torch.mul(csrc, 1.0, out=cdst), 10) / 10
-    ceiling = {"kind": "torch elementwise copy of 1 GiB (1 GiB read + 1 GiB written)",
-               "GB/s": round(2 * (1 << 30) / cms / 1e6, 1),
-               "frac_hbm": round(2 * (1 << 30) / cms / 1e6 / HBM_PEAK_GBS, 4)}
-    del csrc, cdst
+    ceiling = {"read_only_stream_4GiB": {"kind": "pdelta_probe_read_stream: 16-byte loads, every byte once, no writes",
+                                         "GB/s": round((1 << 32) / rms / 1e6, 1),
+                                         "frac_hbm": round((1 << 32) / rms / 1e6 / HBM_PEAK_GBS, 4)},
+               "read_only_stream_per_launch_of_decode_layer_size": {
+                   "bytes_per_launch": piece, "us": round(pms * 1e3, 3), "GB/s": round(piece / pms / 1e6, 1),
+                   "frac_hbm": round(piece / pms / 1e6 / HBM_PEAK_GBS, 4),
+                   "note": "the floor of any kernel launched once per 4096 x 4096 layer on this box"},
+               "copy_1GiB": {"kind": "torch elementwise copy of 1 GiB (1 GiB read + 1 GiB written)",
+                             "GB/s": round(2 * (1 << 30) / cms / 1e6, 1),
+                             "frac_hbm": round(2 * (1 << 30) / cms / 1e6 / HBM_PEAK_GBS, 4)}}
+    del csrc, cdst, big
     torch.cuda.empty_cache()
+    mfma_ceiling = {"kind": "pdelta_probe_mfma: 256 workgroups, v_mfma_f32_32x32x16_f16 only"}
+    for wps in (1, 2):
+        for rnd in (False, True):
+            fl = pd.pdelta_probe_mfma(wps, rnd, 2000, sink)
+            mms = timed(lambda: pd.pdelta_probe_mfma(wps, rnd, 20000, sink), 2) / 2
+            mfma_ceiling[f"{wps}_waves_per_simd_{'random' if rnd else 'constant'}_operands_TFLOP/s"] = round(
+                fl * 10 / mms / 1e9, 1)
 
     out = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
@@ -203,7 +260,10 @@ def main() -> int:
                                "the K steps replayed from one HIP graph",
                    "bytes_per_step": step_bytes},
         "roofline": roofline, "decode_cases": per_case, "wall_s_timed_region": round(wall_s, 4),
-        "device": device_info, "achieved_ceiling": ceiling,
+        "timed_replays": {"count": len(replays_ms), "ms_per_step_min": round(replays_ms[0] / args.steps, 5),
+                          "ms_per_step_median": round(ms_per_step, 5),
+                          "ms_per_step_max": round(replays_ms[-1] / args.steps, 5)},
+        "device": device_info, "achieved_ceiling": ceiling, "mfma_ceiling": mfma_ceiling,
     }
     # ---------------- multi-variant decode: R requests share W_b, each has its own delta -------
     if "variants" not in skip:
@@ -493,22 +553,82 @@ def main() -> int:
     layers = None
     torch.cuda.empty_cache()
 
-    # ---------------- CPU oracle on a bounded sample of the decode workload --------------------
+    # ---------------- CPU oracle on bounded samples of the workloads ---------------------------
     if "cpu" not in skip:
+        import ctypes
+        import platform
         from oracle import pdelta_oracle as orc
+        all_threads = orc.threads()
+
+        def set_threads(n):
+            ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+        cpu_model = platform.processor() or ""
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
         L = synth.layer_host(N, K, 16, synth.F16, "row", synth.seed_for(1, 0))
         Bo, vr, vc = orc.pack(L["dW"], np.zeros_like(L["dW"]))
-        reps = 12
-        t0 = time.perf_counter()
-        for _ in range(reps):
+
+        def decode_pass():
             for axis, M in cases:
                 orc.linear(L["X"][:M], L["W_b"], Bo, vr if axis == "row" else vc,
                            orc.ROW if axis == "row" else orc.COL)
+
+        reps = 0
+        t0 = time.perf_counter()
+        while reps < 2 or (time.perf_counter() - t0 < 10.0 and reps < 16):     # about 10 s of CPU work
+            decode_pass()
+            reps += 1
         dt = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(reps * step_bytes / dt / 1e9, 4), "unit": "GB/s",
-                               "cores": orc.threads(), "kind": "oracle",
-                               "sample": f"{reps} passes of the same 4-launch decode step on one buffer set "
-                                         f"(fp64, dense W_hat rebuilt per call), {dt:.1f} s"}
+        set_threads(1)
+        t0 = time.perf_counter()
+        decode_pass()
+        dt1 = time.perf_counter() - t0
+        set_threads(all_threads)
+        cpu = {"value": round(reps * step_bytes / dt / 1e9, 4), "unit": "GB/s", "cores": all_threads, "kind": "oracle",
+               "sample": f"{reps} passes of the same 4-launch decode step on one buffer set "
+                         f"(fp64, dense W_hat rebuilt per call), {dt:.1f} s",
+               "one_thread": {"value": round(step_bytes / dt1 / 1e9, 4), "unit": "GB/s", "cores": 1,
+                              "sample": f"1 pass of the decode step, {dt1:.1f} s"},
+               "cpu_model": cpu_model, "nproc": os.cpu_count()}
+        # configs 2-4: one layer or shape of each kind, scaled to the whole workload (stated per entry)
+        other = {}
+        Lp = synth.layer_host(4096, 4096, 32, synth.BF16, "row", synth.seed_for(2, 1))
+        Bp, vp, _ = orc.pack(Lp["dW"], np.zeros_like(Lp["dW"]), orc.BF16, want_col=False)
+        t0 = time.perf_counter()
+        orc.linear(Lp["X"], Lp["W_b"], Bp, vp, orc.ROW, orc.BF16)
+        dtp = time.perf_counter() - t0
+        flop_sample = 2.0 * 32 * 4096 * 4096
+        flop_cfg2 = sum(2.0 * 2048 * o * i for o, i in synth.PREFILL_SHAPES)
+        other["config2_prefill"] = {"GFLOP/s": round(flop_sample / dtp / 1e9, 2), "cores": all_threads,
+                                    "sample": f"32 tokens x one 4096 x 4096 bf16 layer, {dtp:.2f} s",
+                                    "whole_workload_s_scaled": round(dtp * flop_cfg2 / flop_sample, 1)}
+        t3 = 0.0
+        for d_out, d_in, count in ((4096, 4096, 128), (11008, 4096, 64), (4096, 11008, 32)):
+            Ls = L if (d_out, d_in) == (4096, 4096) else synth.layer_host(d_out, d_in, 1, synth.F16, "row", synth.seed_for(3, d_out))
+            Bs, vs, _ = (Bo, vr, None) if Ls is L else orc.pack(Ls["dW"], np.zeros_like(Ls["dW"]), want_col=False)
+            t0 = time.perf_counter()
+            orc.linear(Ls["X"][:1], Ls["W_b"], Bs, vs, orc.ROW)
+            t3 += (time.perf_counter() - t0) * count
+        other["config3_stack"] = {"tokens/s": round(1.0 / t3, 4), "cores": all_threads,
+                                  "sample": "one layer of each of the three shapes, M = 1, scaled by their counts "
+                                            f"(128 / 64 / 32): {t3:.1f} s per token"}
+        Lw = synth.layer_host(4096, 4096, 1, synth.F16, "row", synth.seed_for(4, 0), zero_frac=0.05, with_wf=True)
+        t0 = time.perf_counter()
+        orc.pack(Lw["W_f"], Lw["W_b"])
+        dtk = time.perf_counter() - t0
+        pack_sample_bytes = 4 * 4096 * 4096 + 4096 * 4096 // 8 + 4 * 4096
+        total_weights = sum(o * i for _, o, i, _ in synth.stack_shapes())
+        other["config4_pack"] = {"GB/s": round(pack_sample_bytes / dtk / 1e9, 3), "cores": 1,
+                                 "sample": f"one 4096 x 4096 fp16 pair (the oracle's pack loops are serial), {dtk:.2f} s",
+                                 "whole_workload_s_scaled": round(dtk * total_weights / (4096 * 4096), 1)}
+        cpu["other_configs"] = other
+        out["cpu_baseline"] = cpu
 
     print(json.dumps(out))
     return 0

@@ -97,6 +97,10 @@ def lib() -> ctypes.CDLL:
         L.pdelta_linear_group.argtypes = [vp, vp, vp, vp, i64, i32, vp, i64, i64, i64, i32, i32, vp]
         L.pdelta_patch_group.restype = i32
         L.pdelta_patch_group.argtypes = [vp, vp, vp, i64, i32, vp, i64, i64, i32, vp]
+        L.pdelta_probe_read_stream.restype = i32
+        L.pdelta_probe_read_stream.argtypes = [vp, sz, vp, vp]
+        L.pdelta_probe_mfma.restype = i32
+        L.pdelta_probe_mfma.argtypes = [i32, i32, i32, vp, vp]
         L.pdelta_status_string.restype = ctypes.c_char_p
         L.pdelta_status_string.argtypes = [i32]
         _lib = L
@@ -476,3 +480,18 @@ def pdelta_patch_group(W_b, B_packed, v, group: int, out=None):
                                   _dev(out, "W_out"), d_out, d_in, dtype_code(W_b.dtype), _stream())
     _check(rc, "pdelta_patch_group")
     return out
+
+
+# ---- bench helpers (include/pdelta_probes.h): what this GPU sustains, not part of the method ----
+
+def pdelta_probe_read_stream(src: torch.Tensor, sink: torch.Tensor):
+    """Enqueue one read-only pass over every byte of ``src`` (16-byte loads)."""
+    rc = lib().pdelta_probe_read_stream(_dev(src, "src"), src.numel() * src.element_size(), _dev(sink, "sink"), _stream())
+    _check(rc, "pdelta_probe_read_stream")
+
+
+def pdelta_probe_mfma(waves_per_simd: int, random_operands: bool, iters: int, sink: torch.Tensor):
+    """Enqueue the matrix-core loop; returns the flops it performs."""
+    rc = lib().pdelta_probe_mfma(waves_per_simd, int(random_operands), iters, _dev(sink, "sink"), _stream())
+    _check(rc, "pdelta_probe_mfma")
+    return 256 * waves_per_simd * 4 * iters * 4 * 32768.0

@@ -13,7 +13,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libpdelta.so")
 
 SOURCES = ["pdelta_api.hip", "pdelta_pack.hip", "pdelta_pack_group.hip", "pdelta_patch.hip", "pdelta_linear_skinny.hip",
-           "pdelta_linear_gemm.hip", "pdelta_linear_variants.hip", "pdelta_grad.hip"]
+           "pdelta_linear_gemm.hip", "pdelta_linear_variants.hip", "pdelta_grad.hip", "pdelta_probes.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -13,9 +13,13 @@ A = 0x10000          # a fake, 16-byte aligned, non-null device address (never d
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "pdelta.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(pdelta_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if header.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", header)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(pdelta_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_function():
@@ -28,6 +32,18 @@ def test_library_exports_every_declared_function():
     L = pd.lib()
     for n in names:
         assert hasattr(L, n), n
+
+
+def test_probe_argument_errors():
+    L = pd.lib()
+    assert L.pdelta_probe_read_stream(None, 1024, A, None) == pd.EINVAL
+    assert L.pdelta_probe_read_stream(A, 0, A + 4096, None) == pd.EINVAL
+    assert L.pdelta_probe_read_stream(A, 1000, A + 4096, None) == pd.ESHAPE
+    assert L.pdelta_probe_read_stream(A + 8, 1024, A + 4096, None) == pd.EALIGN
+    assert L.pdelta_probe_mfma(3, 0, 10, A, None) == pd.EINVAL
+    assert L.pdelta_probe_mfma(2, 2, 10, A, None) == pd.EINVAL
+    assert L.pdelta_probe_mfma(2, 1, 0, A, None) == pd.EINVAL
+    assert L.pdelta_probe_mfma(2, 1, 10, None, None) == pd.EINVAL
 
 
 def test_status_strings():

@@ -31,6 +31,18 @@ def test_bench_prints_one_json_line_with_the_contract_fields():
     assert abs(d["value"] - d["config"]["bytes_per_step"] / (d["ms_per_step"] * 1e-3) / 1e9) / d["value"] < 1e-2
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["unit"] == "GB/s" and c["cores"] >= 1 and c["value"] > 0 and "sample" in c
+    assert c["one_thread"]["cores"] == 1 and c["one_thread"]["value"] > 0 and c["nproc"] >= 1 and "cpu_model" in c
+    assert set(c["other_configs"]) == {"config2_prefill", "config3_stack", "config4_pack"}
+    t = d["timed_replays"]
+    assert t["count"] >= 5 and t["ms_per_step_min"] <= t["ms_per_step_median"] <= t["ms_per_step_max"]
+    assert t["ms_per_step_median"] == d["ms_per_step"]
+    ceil = d["achieved_ceiling"]
+    assert 0.3 < ceil["read_only_stream_4GiB"]["frac_hbm"] <= 1.0
+    assert ceil["read_only_stream_per_launch_of_decode_layer_size"]["us"] > 0
+    m = d["mfma_ceiling"]
+    assert 0 < m["2_waves_per_simd_random_operands_TFLOP/s"] <= 2600.0
+    assert m["2_waves_per_simd_constant_operands_TFLOP/s"] <= 2600.0
+    assert set(("sclk_MHz", "mclk_MHz", "compute_partition", "memory_partition")) <= set(d["device"])
 
 
 def test_bench_refuses_more_than_one_gpu():
