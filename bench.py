@@ -37,21 +37,40 @@ def decode_bytes(d_out: int, d_in: int, M: int, axis: str) -> int:
     return 2 * d_out * d_in + d_out * d_in // 8 + 2 * v_len + 2 * M * d_in + 2 * M * d_out
 
 
-def smi_info() -> dict:
-    """Clocks and partition modes as rocm-smi reports them (a child process; null when unavailable)."""
-    import re
-    import subprocess
+def gpu_sysfs_info() -> dict:
+    """Clock levels and partition modes of the first amdgpu card, read from sysfs (no child process:
+    nothing is executed, so this also works under a profiler).  Entries are null when not exposed."""
+    import glob
     out = {"sclk_MHz": None, "mclk_MHz": None, "compute_partition": None, "memory_partition": None}
-    try:
-        txt = subprocess.run(["rocm-smi", "--showclocks", "--showcomputepartition", "--showmemorypartition"],
-                             capture_output=True, text=True, timeout=30).stdout
-        for key, pat in (("sclk_MHz", r"sclk clock level:\s*\d+:?\s*\(?(\d+)Mhz"), ("mclk_MHz", r"mclk clock level:\s*\d+:?\s*\(?(\d+)Mhz"),
-                         ("compute_partition", r"Compute Partition:\s*(\S+)"), ("memory_partition", r"Memory Partition:\s*(\S+)")):
-            m = re.search(pat, txt, flags=re.I)
-            if m:
-                out[key] = int(m.group(1)) if key.endswith("MHz") else m.group(1)
-    except Exception as exc:                                   # the figures are informative only
-        out["note"] = f"rocm-smi not usable: {str(exc)[:80]}"
+
+    def read(path):
+        try:
+            with open(path) as f:
+                return f.read().strip()
+        except OSError:
+            return None
+
+    def levels(text):
+        # lines like "1: 2400Mhz *": all levels, and the one marked current
+        if not text:
+            return None
+        all_levels, current = [], None
+        for line in text.splitlines():
+            digits = "".join(ch for ch in line.split(":")[-1] if ch.isdigit())
+            if digits:
+                all_levels.append(int(digits))
+                if "*" in line:
+                    current = int(digits)
+        return {"levels": all_levels, "current_when_idle": current} if all_levels else None
+
+    for dev in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+        if read(os.path.join(dev, "vendor")) != "0x1002":
+            continue
+        out["sclk_MHz"] = levels(read(os.path.join(dev, "pp_dpm_sclk")))
+        out["mclk_MHz"] = levels(read(os.path.join(dev, "pp_dpm_mclk")))
+        out["compute_partition"] = read(os.path.join(dev, "current_compute_partition"))
+        out["memory_partition"] = read(os.path.join(dev, "current_memory_partition"))
+        break
     return out
 
 
@@ -206,7 +225,7 @@ def main() -> int:
     device_info = {"name": props.name, "arch": getattr(props, "gcnArchName", ""),
                    "compute_units": props.multi_processor_count,
                    "memory_GiB": round(props.total_memory / 2 ** 30, 1)}
-    device_info.update(smi_info())
+    device_info.update(gpu_sysfs_info())
     sink = torch.zeros(64, dtype=torch.uint8, device=dev)
     big = torch.empty(1 << 32, dtype=torch.uint8, device=dev)            # 4 GiB, read-only stream
     big.view(torch.int32).fill_(0x01020304)

@@ -307,7 +307,15 @@ int pdelta_patch_batch(const pdelta_layer* layers_host, const pdelta_layer* laye
         if (L.first_block != (int32_t)first) return PDELTA_EINVAL;     // not planned, or edited
         first += (L.d_out + 15) / 16;
     }
-    const int rc = launch_patch_batch(w_dtype, layers_host, layers_device, n_layers, (hipStream_t)stream);
+    int rc = launch_patch_batch(w_dtype, layers_host, layers_device, n_layers, (hipStream_t)stream);
+    if (rc == 1) {                                                      // too many blocks for one grid
+        rc = 0;
+        for (int32_t l = 0; l < n_layers && rc == 0; ++l) {
+            const pdelta_layer& L = layers_host[l];
+            rc = launch_patch_dispatch(w_dtype, L.axis, L.W_b, L.B_packed, L.v, L.Y, L.d_out, L.d_in,
+                                       (hipStream_t)stream);
+        }
+    }
     return rc == 0 ? PDELTA_OK : PDELTA_EHIP;
 }
 

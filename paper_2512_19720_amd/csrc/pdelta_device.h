@@ -84,6 +84,27 @@ __device__ __forceinline__ uint32_t f64_to_bf16_bits_rne(double x) {
 __device__ __forceinline__ half2v as_half2(uint32_t u) { return __builtin_bit_cast(half2v, u); }
 __device__ __forceinline__ uint32_t as_u32(half2v h) { return __builtin_bit_cast(uint32_t, h); }
 
+// A pointer that a kernel read out of a descriptor in memory is a generic ("flat") pointer to the
+// compiler: its loads become flat_load, whose completion counters are shared with LDS, so every
+// wait on them is a wait for ALL outstanding loads and a ring of loads in flight degenerates to
+// one batch at a time.  Descriptors of this library only ever hold device-global addresses;
+// saying so turns the accesses into global_load / global_store with counted waits.
+// (The empty asm statement keeps the optimizer from folding the pair of casts away.)
+// as_global: for pointers that are uniform across the wavefront (held in scalar registers);
+// as_global_per_lane: for pointers that differ between lanes.
+template <typename T>
+__device__ __forceinline__ T* as_global(T* p) {
+    __attribute__((address_space(1))) T* g = (__attribute__((address_space(1))) T*)p;
+    asm volatile("" : "+s"(g));
+    return (T*)g;
+}
+template <typename T>
+__device__ __forceinline__ T* as_global_per_lane(T* p) {
+    __attribute__((address_space(1))) T* g = (__attribute__((address_space(1))) T*)p;
+    asm volatile("" : "+v"(g));
+    return (T*)g;
+}
+
 // ---- wavefront reductions -------------------------------------------------------------------
 
 __device__ __forceinline__ float wave_sum(float x) {

@@ -506,11 +506,13 @@ linear_skinny_batch_kernel(const pdelta_layer* __restrict__ layers, int n_layers
     const pdelta_layer L = layers[lo];
     const int block = b - L.first_block;
     if (L.axis == 0)
-        staged_body<XDT, 0, WAVES, DEPTH, STAGE_X>((const uint16_t*)L.X, (const uint16_t*)L.W_b, L.B_packed,
-                                                L.v, L.Y, M, (int)L.d_out, (int)L.d_in, y_dtype, block);
+        staged_body<XDT, 0, WAVES, DEPTH, STAGE_X>(as_global((const uint16_t*)L.X), as_global((const uint16_t*)L.W_b),
+                                                as_global(L.B_packed), as_global(L.v), as_global(L.Y), M,
+                                                (int)L.d_out, (int)L.d_in, y_dtype, block);
     else
-        staged_body<XDT, 1, WAVES, DEPTH, STAGE_X>((const uint16_t*)L.X, (const uint16_t*)L.W_b, L.B_packed,
-                                                L.v, L.Y, M, (int)L.d_out, (int)L.d_in, y_dtype, block);
+        staged_body<XDT, 1, WAVES, DEPTH, STAGE_X>(as_global((const uint16_t*)L.X), as_global((const uint16_t*)L.W_b),
+                                                as_global(L.B_packed), as_global(L.v), as_global(L.Y), M,
+                                                (int)L.d_out, (int)L.d_in, y_dtype, block);
 }
 
 constexpr size_t kStagedLdsLimit = 96 * 1024;
@@ -548,7 +550,14 @@ static int try_staged(const void* X, const void* W_b, const uint32_t* B_packed, 
                       void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
                       hipStream_t stream)
 {
-    if (M > 16 || d_in % 128 != 0 || tune_value("skinny_staged", 1) == 0) return 1;
+    if (M > 16 || d_in % 128 != 0) return 1;
+    // Measured on MI355X (4096 x 4096, 11008 x 4096, 4096 x 11008; 1 and 16 tokens): with the plain
+    // kernel's loads in the coalesced lane mapping the staged kernel only wins where it saves real
+    // work, in column mode with X small enough for LDS (fp16(X * v_col) is then formed once per
+    // workgroup instead of once per step: 18.8 against 22.1 us on 11008 x 4096).  Everywhere else
+    // the plain kernel is as fast or up to 6 % faster (no staging phase before the first MFMA).
+    const bool staged_pays = AXIS == 1 && M * d_in <= 24576;
+    if (tune_value("skinny_staged", staged_pays ? 1 : 0) == 0) return 1;
     // Measured on MI355X: 8 waves with 2 steps in flight each is the best general choice; when a
     // layer is wide (d_in >= 8192) but has few workgroups (<= 2 per CU) 16 waves fill the CU better.
     const bool wide_few = d_in >= 8192 && (d_out + 15) / 16 <= 512;
@@ -604,7 +613,9 @@ static int launch_by_tokens(const void* X, const void* W_b, const uint32_t* B_pa
 #define PDELTA_GO(MT, WAVES, DEPTH) \
     return launch_one<XDT, AXIS, MT, WAVES, DEPTH, K128>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream)
     const int waves = tune_value("skinny_waves", 8);
-    const int depth = tune_value("skinny_depth", 2);
+    // steps in flight per wave: two, except row mode at more than 8 tokens, where one is 3-4 %
+    // faster (measured; the X loads double the bytes in flight per step)
+    const int depth = tune_value("skinny_depth", (AXIS == 0 && M > 8) ? 1 : 2);
     if (M <= 16) {
         if (waves == 4) {
             if (depth == 4) PDELTA_GO(1, 4, 4);

@@ -84,7 +84,7 @@ linear_variants_kernel(const uint16_t* __restrict__ X, const uint16_t* __restric
     // per-request axis: a row-mode request has no scale per input; its loads of "v" read its own
     // X row instead (valid memory of the right length) and the value is replaced by 1.0
     const bool col = AXIS == 1 || (AXIS == 2 && variants[req].axis == PDELTA_COL);
-    const uint16_t* vrow = AXIS == 0 ? nullptr : (col ? variants[req].v + g * 8 : xrow);
+    const uint16_t* vrow = AXIS == 0 ? nullptr : (col ? as_global_per_lane(variants[req].v) + g * 8 : xrow);
     static_assert(STAGE || NQ == 8, "without staging a step keeps the sign words of 8 requests in registers");
     const uint32_t* brow[NQ];                         // this lane's sign row per request
     const int spr = wpr + 4;                          // LDS row stride in words (STAGE)
@@ -92,7 +92,7 @@ linear_variants_kernel(const uint16_t* __restrict__ X, const uint16_t* __restric
     for (int q = 0; q < NQ; ++q) {
         const int r = min(q, R - 1);
         if constexpr (STAGE) brow[q] = s_sign + (r * 16 + n) * spr;
-        else brow[q] = variants[r].B_packed + (int64_t)o * wpr;
+        else brow[q] = as_global(variants[r].B_packed) + (int64_t)o * wpr;
     }
 
     auto load = [&](VarStep& S, int kb) {
@@ -186,7 +186,7 @@ linear_variants_kernel(const uint16_t* __restrict__ X, const uint16_t* __restric
         const int upr = wpr >> 2, per_slot = 16 * upr;
         const uint32_t* slab[NQ];
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) slab[q] = variants[min(q, R - 1)].B_packed;     // uniform
+        for (int q = 0; q < NQ; ++q) slab[q] = as_global(variants[min(q, R - 1)].B_packed);     // uniform
         for (int first = 0; first < per_slot; first += 512) {
             const int i = first + tid;
             const int ic = min(i, per_slot - 1);
@@ -241,7 +241,7 @@ linear_variants_kernel(const uint16_t* __restrict__ X, const uint16_t* __restric
                 delta += red_s[w][t < NQ ? t : 0][nn];
             }
             float scale = 1.0f;
-            if (AXIS == 0 || (AXIS == 2 && variants[t].axis == PDELTA_ROW)) scale = f16_bits_to_f32(variants[t].v[oo]);
+            if (AXIS == 0 || (AXIS == 2 && variants[t].axis == PDELTA_ROW)) scale = f16_bits_to_f32(as_global_per_lane(variants[t].v)[oo]);
             const float sum = base + scale * delta;
             const int64_t yi = (int64_t)t * d_out + oo;
             if (y_dtype == kF32) store_y<kF32>(Y, yi, sum);

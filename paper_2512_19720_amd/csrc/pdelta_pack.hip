@@ -28,6 +28,14 @@ constexpr int kPackChunks = 2;
 constexpr int kPackTileCols = kPackChunk * kPackChunks;      // 1024: 128 B of sign bits per row
 constexpr int kPackTileRows = 64;                            // smallest tile height: bounds the workspace
 constexpr int kPackSignWords = kPackTileCols / 32;           // 32 words per tile row
+// Measured on MI355X (fp16, 7B-shaped layers): the rate of this kernel does not depend on how far
+// ahead a wave loads (1, 2 or 4 rows: 4.4-4.8, 4.3-4.8, 3.7-3.9 TB/s, the last at 3 waves per SIMD),
+// on the tile width (512 or 1024 columns at 4-7 waves per SIMD), on the tile height (64 to 512
+// rows) or on the arithmetic (with the sums and compares taken out it streams at the same
+// 4.5 TB/s; the vector ALUs are 36-42 % busy).  Two rows ahead at 4 waves per SIMD it is.
+constexpr int kPackAhead = 2;                                // rows in flight per wave
+constexpr int kPackOcc = 4;                                  // waves per SIMD the registers allow
+constexpr int kPackBatchWaves = 4;                           // waves per workgroup of the batched kernel
 
 static inline int64_t pack_row_tiles(int64_t d_out) { return (d_out + kPackTileRows - 1) / kPackTileRows; }
 static inline int64_t pack_col_tiles(int64_t d_in) { return (d_in + kPackTileCols - 1) / kPackTileCols; }
@@ -159,13 +167,14 @@ pack_tile(const uint16_t* __restrict__ W_f, const uint16_t* __restrict__ W_b, in
         t += __shfl_xor(t, 2, kWave);
         t += __shfl_xor(t, 1, kWave);
         const int r = lane >> 3, piece = lane & 7;
-        const uint4v words = *(const uint4v*)&s_sign[wave][r][piece * 4];
+        constexpr int kPieces = kPackSignWords / 4;                  // 16-byte pieces of sign words per tile row
+        const uint4v words = *(const uint4v*)&s_sign[wave][r][min(piece, kPieces - 1) * 4];
         wave_sync();
         const int row = first_row + r;
         const int colp = col0 + piece * 128;
         if (row < d_out) {
             if (row_part != nullptr && piece == 0) row_part[(int64_t)col_tile * d_out + row] = t;
-            if (colp < d_in) {
+            if (piece < kPieces && colp < d_in) {
                 uint32_t* dst = B_packed + (int64_t)row * (d_in >> 5) + (colp >> 5);
                 if (rows_aligned) {
                     *(uint4v*)dst = words;
@@ -180,24 +189,24 @@ pack_tile(const uint16_t* __restrict__ W_f, const uint16_t* __restrict__ W_b, in
 
     // two rows in flight; the scheduling fences keep the compiler from interleaving the
     // arithmetic of different rows (which costs registers and gains nothing: HBM-bound)
-    PackRow buf[2];
-    load(buf[0], row0);
-    load(buf[1], row0 + 1);
+    PackRow buf[kPackAhead];
+#pragma unroll
+    for (int a = 0; a < kPackAhead; ++a) load(buf[a], row0 + a);
     __builtin_amdgcn_sched_barrier(0);
     int row = row0;
     for (int blk = 0; blk + 1 < blocks; ++blk, row += 8) {
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            compute(buf[r & 1], r);
-            load(buf[r & 1], row + r + 2);
+            compute(buf[r % kPackAhead], r);
+            load(buf[r % kPackAhead], row + r + kPackAhead);
             __builtin_amdgcn_sched_barrier(0);
         }
         flush(row);
     }
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {                    // last block: nothing left to load after row 5
-        compute(buf[r & 1], r);
-        if (r < 6) load(buf[r & 1], row + r + 2);
+    for (int r = 0; r < 8; ++r) {                    // last block: nothing left to load near its end
+        compute(buf[r % kPackAhead], r);
+        if (r < 8 - kPackAhead) load(buf[r % kPackAhead], row + r + kPackAhead);
         __builtin_amdgcn_sched_barrier(0);
     }
     flush(row);
@@ -221,7 +230,7 @@ pack_tile(const uint16_t* __restrict__ W_f, const uint16_t* __restrict__ W_b, in
 }
 
 template <int DT, int WAVES>
-__global__ void __launch_bounds__(WAVES * kWave, 4)     // 4 waves per SIMD
+__global__ void __launch_bounds__(WAVES * kWave, kPackOcc)
 pack_main_kernel(const uint16_t* __restrict__ W_f, const uint16_t* __restrict__ W_b,
                  int d_out, int d_in, uint32_t* __restrict__ B_packed,
                  double* __restrict__ row_part, double* __restrict__ col_part, int blocks,
@@ -235,7 +244,7 @@ pack_main_kernel(const uint16_t* __restrict__ W_f, const uint16_t* __restrict__ 
 
 // Many layers in one launch: workgroup b works on the last job whose first_tile is <= b.
 template <int DT>
-__global__ void __launch_bounds__(4 * kWave, 4)
+__global__ void __launch_bounds__(kPackBatchWaves * kWave, kPackOcc)
 pack_main_batch_kernel(const pdelta_pack_job* __restrict__ jobs, int n_jobs)
 {
     const int b = (int)blockIdx.x;
@@ -248,9 +257,10 @@ pack_main_batch_kernel(const pdelta_pack_job* __restrict__ jobs, int n_jobs)
     const int id = b - J.first_tile;
     const int d_out = (int)J.d_out, d_in = (int)J.d_in;
     const int n_ct = (d_in + kPackTileCols - 1) / kPackTileCols;
-    double* row_part = (double*)J.workspace;
+    double* row_part = as_global((double*)J.workspace);
     double* col_part = row_part + (int64_t)n_ct * d_out;
-    pack_tile<DT, 4>((const uint16_t*)J.W_f, (const uint16_t*)J.W_b, d_out, d_in, J.B_packed,
+    pack_tile<DT, kPackBatchWaves>(as_global((const uint16_t*)J.W_f), as_global((const uint16_t*)J.W_b), d_out, d_in,
+                     as_global(J.B_packed),
                      J.v_row ? row_part : (double*)nullptr, J.v_col ? col_part : (double*)nullptr,
                      id / n_ct, id % n_ct, J.tile_blocks);
 }
@@ -328,11 +338,11 @@ pack_finalize_batch_kernel(const pdelta_pack_job* __restrict__ jobs, int n_jobs)
     const pdelta_pack_job J = jobs[lo];
     const int d_out = (int)J.d_out, d_in = (int)J.d_in;
     const int n_ct = (d_in + kPackTileCols - 1) / kPackTileCols;
-    const int tile_rows = 32 * J.tile_blocks;
+    const int tile_rows = kPackBatchWaves * 8 * J.tile_blocks;
     const int n_rt = (d_out + tile_rows - 1) / tile_rows;
-    const double* row_part = (const double*)J.workspace;
+    const double* row_part = as_global((const double*)J.workspace);
     const double* col_part = row_part + (int64_t)n_ct * d_out;
-    pack_finalize_block<DT>(row_part, col_part, n_ct, n_rt, d_out, d_in, J.v_row, J.v_col,
+    pack_finalize_block<DT>(row_part, col_part, n_ct, n_rt, d_out, d_in, as_global(J.v_row), as_global(J.v_col),
                             b - J.first_fin_block);
 }
 
@@ -376,10 +386,15 @@ static int launch_pack(const void* W_f, const void* W_b, int64_t d_out, int64_t 
 
 // Tiles of a job in the batched kernels: 4 waves x tile_blocks blocks of 8 rows, 1024 columns
 // (512-row tiles for tall layers: fewest column partials, measured 5 % faster than 128 rows).
-int pack_batch_tile_blocks(int64_t d_out) { return d_out >= 2048 ? 16 : (d_out >= 512 ? 4 : 2); }
+int pack_batch_tile_blocks(int64_t d_out)
+{
+    const int blocks = tune_value("pack_batch_blocks", d_out >= 2048 ? 16 : (d_out >= 512 ? 4 : 2));
+    const int least = kPackTileRows / (kPackBatchWaves * 8);        // 64-row tiles at least: the workspace is sized for them
+    return blocks < least ? least : blocks;
+}
 int64_t pack_batch_tiles(int64_t d_out, int64_t d_in, int tile_blocks)
 {
-    const int64_t tile_rows = 32 * tile_blocks;
+    const int64_t tile_rows = kPackBatchWaves * 8 * tile_blocks;
     return ((d_out + tile_rows - 1) / tile_rows) * pack_col_tiles(d_in);
 }
 int64_t pack_batch_fin_blocks(int64_t d_out, int64_t d_in) { return (d_out + 63) / 64 + (d_in + 63) / 64; }
@@ -393,10 +408,10 @@ int launch_pack_batch(int w_dtype, const pdelta_pack_job* jobs_host, const pdelt
     bool want_any = false;
     for (int j = 0; j < n_jobs; ++j) want_any = want_any || jobs_host[j].v_row || jobs_host[j].v_col;
     if (w_dtype == kBF16)
-        hipLaunchKernelGGL(pack_main_batch_kernel<kBF16>, dim3((unsigned)tiles), dim3(4 * kWave), 0, stream,
+        hipLaunchKernelGGL(pack_main_batch_kernel<kBF16>, dim3((unsigned)tiles), dim3(kPackBatchWaves * kWave), 0, stream,
                            jobs_device, n_jobs);
     else
-        hipLaunchKernelGGL(pack_main_batch_kernel<kF16>, dim3((unsigned)tiles), dim3(4 * kWave), 0, stream,
+        hipLaunchKernelGGL(pack_main_batch_kernel<kF16>, dim3((unsigned)tiles), dim3(kPackBatchWaves * kWave), 0, stream,
                            jobs_device, n_jobs);
     if (want_any) {
         if (w_dtype == kBF16)
