@@ -31,7 +31,9 @@ def make_variants(d_out, d_in, R, dtype, axis, seed):
 @pytest.mark.parametrize("R", [1, 3, 8, 9, 16])
 @pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
 @pytest.mark.parametrize("axis", [orc.ROW, orc.COL])
-def test_fused_kernel_matches_oracle(R, dtype, axis):
+@pytest.mark.parametrize("kernel", [1, 2])
+def test_fused_kernel_matches_oracle(R, dtype, axis, kernel, monkeypatch):
+    monkeypatch.setenv("PDELTA_TUNE", f"var_kernel={kernel}")          # 1: slab kernel, 2: stride kernel
     for d_out, d_in in ((64, 256), (100, 1152), (7, 128)):
         X, W_b, Bs, vs, d = make_variants(d_out, d_in, R, dtype, axis, synth.seed_for(1, 3000 + 17 * R + d_out))
         ref = orc.linear_variants(X, W_b, Bs, vs, axis, dtype)
@@ -60,18 +62,20 @@ def test_decode_layer_4096_sixteen_variants(axis):
         assert torch.allclose(single[0], Y[r], rtol=2e-3, atol=2e-3 * float(Y[r].abs().mean()))
 
 
-@pytest.mark.parametrize("R,d_in,stage", [(7, 11008, 1), (20, 384, 0), (33, 256, 1), (5, 128, 0)])
-def test_chunked_launches_and_sign_words_in_registers(R, d_in, stage, monkeypatch):
-    # d_in = 11008: only six sign slabs fit in LDS, so 7 requests take two passes; stage = 0
-    # forces the variant that keeps the sign words in registers (8 requests per pass)
-    monkeypatch.setenv("PDELTA_TUNE", f"var_stage={stage}")
+@pytest.mark.parametrize("R,d_in,kernel", [(7, 11008, 0), (16, 11008, 0), (20, 384, 2), (33, 256, 1), (5, 128, 2),
+                                           (12, 1152, 2), (16, 2176, 2)])
+def test_chunks_of_sixteen_and_both_kernels(R, d_in, kernel, monkeypatch):
+    # kernel 0: chosen by size (d_in = 11008: only six whole sign slabs fit in LDS, so 7 and more
+    # requests go to the stride kernel); 1: slab kernel; 2: stride kernel forced, also on inputs of
+    # 1 to 17 strides with a ragged last one (d_in = 128 ... 2176) and more than 16 requests
+    monkeypatch.setenv("PDELTA_TUNE", f"var_kernel={kernel}")
     d_out = 40
     for axis in (orc.ROW, orc.COL):
         X, W_b, Bs, vs, d = make_variants(d_out, d_in, R, synth.F16, axis, synth.seed_for(1, 6000 + R))
         ref = orc.linear_variants(X, W_b, Bs, vs, axis, synth.F16)
         Y = pd.pdelta_linear_variants(d["X"], d["W_b"], pd.VariantSet(d["variants"], axis), out_dtype=torch.float32)
         torch.cuda.synchronize()
-        check_y(Y, ref, f"chunked R={R} d_in={d_in} stage={stage} axis={axis}")
+        check_y(Y, ref, f"chunked R={R} d_in={d_in} kernel={kernel} axis={axis}")
 
 
 @pytest.mark.parametrize("R,d_in", [(17, 160), (4, 160), (20, 96)])
@@ -106,8 +110,9 @@ def test_one_axis_per_request(R, dtype, monkeypatch):
     rng = np.random.default_rng(40 + R)
     axes = [int(a) for a in rng.integers(0, 2, R)]
     axes[0], axes[1] = orc.ROW, orc.COL                                # both modes are present
-    for d_out, d_in, tune in ((100, 1152, ""), (64, 4096, ""), (40, 384, "var_stage=0"), (48, 160, "")):
-        monkeypatch.setenv("PDELTA_TUNE", tune)                        # fused (staged / in registers) and fallback paths
+    for d_out, d_in, tune in ((100, 1152, ""), (64, 4096, ""), (40, 384, "var_kernel=2"), (100, 1152, "var_kernel=2"),
+                              (48, 160, "")):
+        monkeypatch.setenv("PDELTA_TUNE", tune)                        # fused (slab / stride kernel) and fallback paths
         X, W_b, Bs, vs, d = make_mixed(d_out, d_in, axes, dtype, synth.seed_for(1, 7000 + R + d_out))
         ref = orc.linear_variants(X, W_b, Bs, vs, axes, dtype)
         vset = pd.VariantSet(d["variants"], axes)
