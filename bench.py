@@ -12,7 +12,7 @@ each with its own events, the other workloads of the path (prefill GEMM shapes, 
 decode stack, the offline pack of that stack, the in-place patch) and the CPU oracle on a
 bounded sample; they are reported as extra objects on the same JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--skip variants,prefill,grad,stack,pack,patch,cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--skip group,variants,prefill,grad,stack,pack,patch,cpu]
 """
 from __future__ import annotations
 
@@ -214,7 +214,7 @@ def main() -> int:
                                   "of this same command, committed as profiles/decode_4096x4096_pmc_traffic.md")
     launches = args.steps * len(cases)
     avg_launch_us = ms_total * 1e3 / launches
-    roofline = {"bound": "hbm", "kernel": "linear_skinny_staged_kernel (decode, 4096x4096 fp16)",
+    roofline = {"bound": "hbm", "kernel": "linear_skinny_kernel / linear_skinny_staged_kernel (decode, 4096x4096 fp16)",
                 "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(value / HBM_PEAK_GBS, 4),
                 "bytes_per_launch": step_bytes // len(cases),
@@ -284,6 +284,29 @@ def main() -> int:
                           "ms_per_step_max": round(replays_ms[-1] / args.steps, 5)},
         "device": device_info, "achieved_ceiling": ceiling, "mfma_ceiling": mfma_ceiling,
     }
+    # ---------------- blockwise and scalar scales on the same decode layer ----------------------
+    if "group" not in skip:
+        res = {"workload": "decode GEMV 4096x4096 fp16, M = 1, scales per (row, block of 128 inputs) / one scalar per matrix; "
+                           f"{args.sets} rotating buffer sets", "entry_point": "pdelta_linear_group"}
+        for name, group, shared in (("group_128", 128, False), ("scalar", K, True)):
+            n_groups = K // group
+            vg = torch.full((1 if shared else N, n_groups), 1e-3, dtype=f16, device=dev)
+            grot = [0]
+
+            def group_call():
+                W_b, B, _, _ = sets[grot[0] % len(sets)]
+                grot[0] += 1
+                pd.pdelta_linear_group(X1, W_b, B, vg, group, out=Y1)
+
+            gg = graph_of(group_call, 200)
+            timed(gg.replay, 1)
+            ms = sorted(timed(gg.replay, 1) for _ in range(5))[2] / 200
+            gb = 2 * N * K + N * K // 8 + 2 * vg.numel() + 2 * K + 2 * N
+            res[name] = {"us": round(ms * 1e3, 3), "GB/s": round(gb / ms / 1e6, 1),
+                         "frac_hbm": round(gb / ms / 1e6 / HBM_PEAK_GBS, 4)}
+            del gg
+        out["group_scales"] = res
+
     # ---------------- multi-variant decode: R requests share W_b, each has its own delta -------
     if "variants" not in skip:
         R, nsets = 16, 12                       # 12 x (32 MiB W_b + 16 x 2 MiB signs) = 768 MiB
