@@ -96,13 +96,13 @@ def test_empty_batch_is_a_no_op():
 
 
 @pytest.mark.parametrize("shape", synth.PREFILL_SHAPES)
-@pytest.mark.parametrize("kernel", ["default", "pipelined"])
+@pytest.mark.parametrize("kernel", ["default", "two_per_cu"])
 def test_config2_prefill_full_size_sampled_outputs(shape, kernel, monkeypatch):
     """bf16, M = 2048, the benchmark's launch configuration (the library's own choice of kernel,
-    and the pipelined kernel forced); 600 sampled outputs, each an fp64 dot product by the
+    which is the pipelined one, and the two-per-CU kernel forced); 600 sampled outputs, each an fp64 dot product by the
     oracle, plus whole rows and columns of the output tile grid's corners."""
-    if kernel == "pipelined":
-        monkeypatch.setenv("PDELTA_TUNE", "gemm_pipe=1")
+    if kernel == "two_per_cu":
+        monkeypatch.setenv("PDELTA_TUNE", "gemm_pipe=0")
     d_out, d_in = shape
     M = 2048
     seed = synth.seed_for(2, d_out % 1000 + d_in % 1000)
@@ -151,13 +151,13 @@ def whole_row_reference(shape):
 
 
 @pytest.mark.parametrize("shape", synth.PREFILL_SHAPES)
-@pytest.mark.parametrize("kernel", ["default", "pipelined"])
+@pytest.mark.parametrize("kernel", ["default", "two_per_cu"])
 def test_config2_prefill_full_size_whole_rows(shape, kernel, monkeypatch):
     """bf16, M = 2048, the benchmark's launch configuration: at least 64 whole rows of Y against
     the fp64 oracle, fp32 output under the stated bounds and bf16 output under the bounds widened
     by the final rounding; the packed signs and scales the GPU used are the oracle's, bit for bit."""
-    if kernel == "pipelined":
-        monkeypatch.setenv("PDELTA_TUNE", "gemm_pipe=1")
+    if kernel == "two_per_cu":
+        monkeypatch.setenv("PDELTA_TUNE", "gemm_pipe=0")
     seed, m_rows, Bo, vo, ref = whole_row_reference(shape)
     d_out, d_in = shape
     Ld = synth.layer_device(d_out, d_in, synth.BF16, "row", seed, DEV)
