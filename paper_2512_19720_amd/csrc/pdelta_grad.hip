@@ -181,6 +181,178 @@ grad_tile_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ G,
     }
 }
 
+// Pipelined form of grad_tile_kernel, organised like the prefill kernel of the same tile: one
+// workgroup per CU, two LDS stages and two register sets.  During step s a wave multiplies stage
+// s % 2 and, between its groups of four MFMAs, stages the operands of step s+1 (loaded one step
+// earlier) into the other stage while the loads of step s+2 are in flight: one barrier per step.
+struct GradRegs {
+    uint4v ag[4];
+    uint32_t sb[2];
+};
+
+template <int DT>
+__global__ void __launch_bounds__(512, 2)
+grad_tile_pipe_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ G,
+                      const uint32_t* __restrict__ bits, float* __restrict__ partial, int M, int Nc, int Kc,
+                      int m_tiles)
+{
+    constexpr int BM = kGradBM, BN = kGradBN, BK = kGradBK, LDK = kGradLDK, ROWS = 64, XQ = 4, WQ = 2;
+    constexpr int AS = BM * LDK, STAGE = (BM + BN) * LDK;                 // halves
+    extern __shared__ __attribute__((aligned(16))) unsigned char grad_smem[];
+    uint16_t* lds = (uint16_t*)grad_smem;                                 // [2][STAGE]: A tile then sign tile
+
+    const int tile_m = blockIdx.x % m_tiles, tile_n = blockIdx.x / m_tiles;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    const int ld_row = tid >> 3, ld_c = (tid & 7) * 8;
+    const char* abase = (const char*)(A + (int64_t)m0 * Kc);
+    const char* sbase = (const char*)bits + (((int64_t)n0 * Kc) >> 3);
+    uint32_t aoff[XQ], soff[WQ];
+#pragma unroll
+    for (int q = 0; q < XQ; ++q) {
+        const int row = min(m0 + ld_row + ROWS * q, M - 1) - m0;
+        aoff[q] = ((uint32_t)row * (uint32_t)Kc + (uint32_t)ld_c) * 2u;
+    }
+#pragma unroll
+    for (int q = 0; q < WQ; ++q) {
+        const int row = min(n0 + ld_row + ROWS * q, Nc - 1) - n0;
+        soff[q] = (uint32_t)row * (uint32_t)(Kc >> 3) + (uint32_t)(tid & 7);
+    }
+    const uint4v zero = {0, 0, 0, 0};
+    auto load_global = [&](GradRegs& R, int kb, auto guard) {
+        constexpr bool GUARD = decltype(guard)::value;
+        const bool col_ok = !GUARD || kb + ld_c < Kc;
+        const char* ab = abase + (int64_t)kb * 2;
+        const char* sp = sbase + (kb >> 3);
+#pragma unroll
+        for (int q = 0; q < XQ; ++q) R.ag[q] = col_ok ? *(const uint4v*)(ab + aoff[q]) : zero;
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) R.sb[q] = col_ok ? (uint32_t) * (const uint8_t*)(sp + soff[q]) : 0xFFu;
+    };
+    // quarter c of the staging work of one step
+    auto stage_part = [&](const GradRegs& R, uint16_t* stage, int c) {
+        if (c < 2) {
+            *(uint4v*)(stage + AS + (ld_row + ROWS * c) * LDK + ld_c) = grad_expand<DT>(R.sb[c]);
+            *(uint4v*)(stage + (ld_row + ROWS * c) * LDK + ld_c) = R.ag[c];
+        } else {
+            *(uint4v*)(stage + (ld_row + ROWS * c) * LDK + ld_c) = R.ag[c];
+        }
+    };
+
+    float16v acc[2][2];
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[f][h][r] = 0.f;
+
+    const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+    const int a_off = (wm * 64 + frag_row) * LDK + frag_k;
+    const int b_off = AS + (wn * 64 + frag_row) * LDK + frag_k;
+    auto step = [&](const uint16_t* rd, uint16_t* wr, const GradRegs& Rnext, bool stage_next) {
+        uint4v a[2][2], b[2][2];
+#pragma unroll
+        for (int f = 0; f < 2; ++f) a[0][f] = *(const uint4v*)(rd + a_off + f * 32 * LDK);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) b[0][h] = *(const uint4v*)(rd + b_off + h * 32 * LDK);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+#pragma unroll
+            for (int f = 0; f < 2; ++f)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) acc[f][h] = grad_mfma<DT>(a[cur][f], b[cur][h], acc[f][h]);
+            if (ks + 1 < BK / 16) {
+#pragma unroll
+                for (int f = 0; f < 2; ++f) a[nxt][f] = *(const uint4v*)(rd + a_off + f * 32 * LDK + (ks + 1) * 16);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) b[nxt][h] = *(const uint4v*)(rd + b_off + h * 32 * LDK + (ks + 1) * 16);
+            }
+            if (stage_next) stage_part(Rnext, wr, ks);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    const int full_steps = Kc / BK;
+    const int n_steps = full_steps + ((Kc % BK) != 0 ? 1 : 0);
+    auto load_any = [&](GradRegs& R, int s) {
+        if (s < full_steps) load_global(R, s * BK, std::false_type{});
+        else load_global(R, s * BK, std::true_type{});
+    };
+    uint16_t* st0 = lds;
+    uint16_t* st1 = lds + STAGE;
+    GradRegs R0, R1;
+    load_any(R0, 0);
+    if (n_steps > 1) load_any(R1, 1);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) stage_part(R0, st0, c);
+    __syncthreads();
+
+    int s = 0;
+    // steady state, two steps per iteration (stages and register sets static); the loads are
+    // unconditional and unguarded, so that their waits stay as deep as the pipeline
+    for (; s + 3 < full_steps; s += 2) {
+        load_global(R0, (s + 2) * BK, std::false_type{});
+        __builtin_amdgcn_sched_barrier(0);
+        step(st0, st1, R1, true);
+        __syncthreads();
+        load_global(R1, (s + 3) * BK, std::false_type{});
+        __builtin_amdgcn_sched_barrier(0);
+        step(st1, st0, R0, true);
+        __syncthreads();
+    }
+    // the last (up to three, possibly one partial) steps
+    for (; s < n_steps; ++s) {
+        const bool even = (s & 1) == 0;
+        if (s + 2 < n_steps) {
+            if (even) load_any(R0, s + 2); else load_any(R1, s + 2);
+        }
+        const bool more = s + 1 < n_steps;
+        if (even) step(st0, st1, R1, more); else step(st1, st0, R0, more);
+        __syncthreads();
+    }
+
+    // epilogue as in grad_tile_kernel (every step ended with a barrier: the stages are free)
+    float* red = (float*)lds;                          // [4 wm][128]
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int n = n0 + wn * 64 + h * 32 + (lane & 31);
+        const int nc = min(n, Nc - 1);
+        float sum = 0.f;
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int tok = m0 + wm * 64 + f * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                const uint32_t gbits = G[(int64_t)min(tok, M - 1) * Nc + nc];
+                const float gval = tok < M ? bits_to_f32<DT>(gbits) : 0.f;
+                sum += gval * acc[f][h][r];
+            }
+        sum += __shfl_xor(sum, 32, kWave);
+        if (lane < 32) red[wm * BN + wn * 64 + h * 32 + lane] = sum;
+    }
+    __syncthreads();
+    if (tid < BN) {
+        const int n = n0 + tid;
+        if (n < Nc) partial[(int64_t)tile_m * Nc + n] = (red[tid] + red[BN + tid]) + (red[2 * BN + tid] + red[3 * BN + tid]);
+    }
+}
+
+template <int DT>
+static int launch_grad_tile_pipe(const uint16_t* A, const uint16_t* G, const uint32_t* bits, float* partial,
+                                 int M, int Nc, int Kc, int m_tiles, unsigned grid, hipStream_t stream)
+{
+    constexpr size_t lds = (size_t)2 * (kGradBM + kGradBN) * kGradLDK * sizeof(uint16_t);   // 110,592 bytes
+    auto kernel = grad_tile_pipe_kernel<DT>;
+    static unsigned lds_opted_in = 0;                 // per template instance: one kernel
+    if (opt_in_dynamic_lds((const void*)kernel, (int)lds, &lds_opted_in) != 0) return -1;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(512), lds, stream, A, G, bits, partial, M, Nc, Kc, m_tiles);
+    return 0;
+}
+
 __global__ void __launch_bounds__(256)
 grad_reduce_kernel(const float* __restrict__ partial, float* __restrict__ grad, int n, int m_tiles)
 {
@@ -248,6 +420,12 @@ int launch_grad_v(int dtype, int axis, const void* X, const void* dY, const uint
     const dim3 grid((unsigned)(m_tiles * n_tiles));
     if (m_tiles == 0) {
         // no tokens: the reduction below writes zeros
+    } else if (tune_value("grad_pipe", 1) != 0) {
+        // the pipelined kernel is the default (grad_pipe=0: the two-workgroups-per-CU kernel)
+        const int rc = dtype == kBF16
+            ? launch_grad_tile_pipe<kBF16>(A, G, bits, partial, (int)M, (int)Nc, (int)Kc, (int)m_tiles, grid.x, stream)
+            : launch_grad_tile_pipe<kF16>(A, G, bits, partial, (int)M, (int)Nc, (int)Kc, (int)m_tiles, grid.x, stream);
+        if (rc != 0) return rc;
     } else if (dtype == kBF16)
         hipLaunchKernelGGL(grad_tile_kernel<kBF16>, grid, dim3(512), 0, stream, A, G, bits, partial, (int)M, (int)Nc,
                            (int)Kc, (int)m_tiles);

@@ -43,7 +43,9 @@ SHAPES = [(1, 32, 32), (5, 64, 96), (300, 160, 224), (257, 128, 64), (1000, 96, 
 @pytest.mark.parametrize("M,d_out,d_in", SHAPES)
 @pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
 @pytest.mark.parametrize("axis", [orc.ROW, orc.COL])
-def test_grad_v_matches_oracle(M, d_out, d_in, dtype, axis):
+@pytest.mark.parametrize("kernel", ["pipelined", "two_per_cu"])
+def test_grad_v_matches_oracle(M, d_out, d_in, dtype, axis, kernel, monkeypatch):
+    monkeypatch.setenv("PDELTA_TUNE", "grad_pipe=1" if kernel == "pipelined" else "grad_pipe=0")
     X, dY, B = make(M, d_out, d_in, dtype, synth.seed_for(2, 7000 + M + d_out))
     ref = orc.grad_v(X, dY, B, axis, dtype)
     ws = torch.full((pd.pdelta_grad_v_workspace_bytes(M, d_out, d_in, axis),), 0xCD, dtype=torch.uint8, device=DEV)
@@ -57,9 +59,12 @@ def test_grad_v_matches_oracle(M, d_out, d_in, dtype, axis):
 
 
 @pytest.mark.parametrize("axis", [orc.ROW, orc.COL])
-def test_grad_v_training_shape_sampled(axis):
+@pytest.mark.parametrize("kernel", ["default", "two_per_cu"])
+def test_grad_v_training_shape_sampled(axis, kernel, monkeypatch):
     """M = 2048 tokens on a 4096 x 4096 layer (the benchmark's shape): the oracle evaluates a
     sample of the entries, each from the rows / columns it needs."""
+    if kernel == "two_per_cu":
+        monkeypatch.setenv("PDELTA_TUNE", "grad_pipe=0")
     M, d_out, d_in = 2048, 4096, 4096
     X, dY, B = make(M, d_out, d_in, synth.BF16, synth.seed_for(2, 7900 + axis))
     got = pd.pdelta_grad_v(to_dev(X, synth.BF16), to_dev(dY, synth.BF16), words_dev(B), axis)
