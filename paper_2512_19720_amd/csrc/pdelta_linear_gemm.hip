@@ -309,7 +309,7 @@ linear_gemm_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ 
 // The scheduling fences pin that interleaving.
 struct GemmRegs {                         // one step of one thread: 4 x 16 B of X, 2 x 16 B of W_b, ...
     uint4v xg[4], wg[2], vcg;
-    uint32_t sb[2];
+    uint32_t sb[2], vg[2];                // sign bytes; blockwise mode: the step's scale per W row
 };
 
 template <int XDT, int AXIS>
@@ -317,7 +317,7 @@ __global__ void __launch_bounds__(512, 2)
 linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
                         const uint32_t* __restrict__ B_packed, const uint16_t* __restrict__ v,
                         void* __restrict__ Y, int M, int d_out, int d_in, int y_dtype, int m_tiles,
-                        int n_tiles)
+                        int n_tiles, int v_stride, int g_shift)
 {
     constexpr int BM = 256, WM = 4, ROWS = 64, XQ = 4, WQ = 2, FM = 2, FN = 2;
     constexpr int XS = BM * kGemmLDK, WS = kGemmBN * kGemmLDK, STAGE = XS + WS;   // halves
@@ -348,6 +348,7 @@ linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restri
         xoff[q] = ((uint32_t)row * (uint32_t)K + (uint32_t)ld_c) * 2u;
     }
     uint32_t vabs_row[WQ], vneg_row[WQ];
+    const uint16_t* vgrow[WQ];           // blockwise mode: the scales of the thread's W rows
 #pragma unroll
     for (int q = 0; q < WQ; ++q) {
         const int row = min(n0 + ld_row + ROWS * q, d_out - 1) - n0;
@@ -359,6 +360,7 @@ linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restri
             vabs_row[q] = aa;
             vneg_row[q] = (h & 0x8000u) ? 0xFFu : 0u;
         }
+        if constexpr (AXIS == 2) vgrow[q] = v + (int64_t)(n0 + row) * v_stride;
     }
     const uint4v zero = {0, 0, 0, 0};
 
@@ -374,6 +376,7 @@ linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restri
         for (int q = 0; q < WQ; ++q) {
             G.wg[q] = col_ok ? *(const uint4v*)(wb + woff[q]) : zero;
             G.sb[q] = col_ok ? (uint32_t) * (const uint8_t*)(sp + soff[q]) : 0xFFu;
+            if constexpr (AXIS == 2) G.vg[q] = col_ok ? (uint32_t)vgrow[q][(kb + ld_c) >> g_shift] : 0u;
         }
         if constexpr (AXIS == 1) G.vcg = col_ok ? *(const uint4v*)(v + kb + ld_c) : zero;
     };
@@ -386,6 +389,9 @@ linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restri
         if constexpr (AXIS == 0) {
             const uint32_t aa = vabs_row[q];
             what = add_signed_scale(w16, ~G.sb[q] ^ vneg_row[q], (uint4v){aa, aa, aa, aa});
+        } else if constexpr (AXIS == 2) {
+            const uint32_t h = G.vg[q], a = h & 0x7FFFu, aa = a | (a << 16);
+            what = add_signed_scale(w16, ~G.sb[q] ^ ((h & 0x8000u) ? 0xFFu : 0u), (uint4v){aa, aa, aa, aa});
         } else {
             uint32_t vsign = 0;
 #pragma unroll
@@ -509,7 +515,7 @@ linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restri
 template <int XDT, int AXIS>
 static int launch_gemm_pipe(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
                             void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
-                            hipStream_t stream)
+                            hipStream_t stream, int v_stride = 0, int g_shift = 31)
 {
     constexpr int BM = 256;
     constexpr size_t lds = (size_t)2 * (BM + kGemmBN) * kGemmLDK * sizeof(uint16_t);   // 110,592 bytes
@@ -521,7 +527,7 @@ static int launch_gemm_pipe(const void* X, const void* W_b, const uint32_t* B_pa
     static unsigned lds_opted_in = 0;                 // per template instance: one kernel
     if (opt_in_dynamic_lds((const void*)kernel, (int)lds, &lds_opted_in) != 0) return -1;
     hipLaunchKernelGGL(kernel, grid, dim3(512), lds, stream, (const uint16_t*)X, (const uint16_t*)W_b,
-                       B_packed, v, Y, (int)M, (int)d_out, (int)d_in, y_dtype, m_tiles, n_tiles);
+                       B_packed, v, Y, (int)M, (int)d_out, (int)d_in, y_dtype, m_tiles, n_tiles, v_stride, g_shift);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -730,18 +736,21 @@ static int launch_gemm_bm(const void* X, const void* W_b, const uint32_t* B_pack
     return launch_gemm<XDT, AXIS, 256, 2>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
 }
 
-// Blockwise scales: the small-tile kernel for under-filled grids, else the 256 x 128 (or, for
-// short batches, 128 x 128) tile kernel with two workgroups per compute unit.
+// Blockwise scales: the small-tile kernel for under-filled grids, the 128 x 128 tile kernel for
+// short batches, else the pipelined 256 x 128 kernel (gemm_pipe=0: two workgroups per compute unit).
 template <int XDT>
 static int launch_gemm_group(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v, void* Y,
                              int64_t M, int64_t d_out, int64_t d_in, int y_dtype, int v_stride, int g_shift,
                              hipStream_t stream)
 {
     const int64_t big_tiles = ((M + 255) / 256) * ((d_out + kGemmBN - 1) / kGemmBN);
-    if (d_in % 64 == 0 && big_tiles <= 128)
+    const int small = tune_value("gemm_small", -1);
+    if (d_in % 64 == 0 && (small == 1 || (small < 0 && big_tiles <= 128)))
         return launch_gemm_small<XDT, 2>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream, v_stride, g_shift);
     if (M <= 128)
         return launch_gemm<XDT, 2, 128, 2>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream, v_stride, g_shift);
+    if (tune_value("gemm_pipe", 1) != 0)
+        return launch_gemm_pipe<XDT, 2>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream, v_stride, g_shift);
     return launch_gemm<XDT, 2, 256, 4>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream, v_stride, g_shift);
 }
 

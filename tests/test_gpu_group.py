@@ -81,6 +81,22 @@ def test_linear_group_matches_oracle(M, d_out, d_in, group, dtype, shared):
         check_y(Y, ref, f"group linear M={M} {d_out}x{d_in} g={group} shared={shared} dt={dtype} y={yd}")
 
 
+@pytest.mark.parametrize("M,d_out,d_in,group", [c for c in LINEAR_CASES if c[0] > 128])
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("kernel", ["pipelined", "two_per_cu"])
+def test_linear_group_big_tile_kernels_forced(M, d_out, d_in, group, dtype, kernel, monkeypatch):
+    """The two 256 x 128 tile kernels on shapes that the dispatch would give to the small-tile kernel."""
+    monkeypatch.setenv("PDELTA_TUNE", "gemm_small=0,gemm_pipe=" + ("1" if kernel == "pipelined" else "0"))
+    L = group_case(d_out, d_in, M, dtype, group, False, synth.seed_for(1, 8300 + M + d_out + group))
+    ref = orc.linear_group(L["X"], L["W_b"], L["B"], L["v"], group, dtype)
+    X, W_b, B, v = to_dev(L["X"], dtype), to_dev(L["W_b"], dtype), words_dev(L["B"]), v_dev(L["v"])
+    for yd in (torch.float32, TORCH16[dtype]):
+        Y = torch.full((M, d_out), float("nan"), dtype=yd, device=DEV)
+        pd.pdelta_linear_group(X, W_b, B, v, group, out=Y)
+        torch.cuda.synchronize()
+        check_y(Y, ref, f"group linear ({kernel}) M={M} {d_out}x{d_in} g={group} dt={dtype} y={yd}")
+
+
 @pytest.mark.parametrize("M", [1, 16, 2048])
 def test_linear_group_on_a_benchmark_layer(M):
     """4096 x 4096 with groups of 128 inputs (the usual block size of group-wise formats) and the
