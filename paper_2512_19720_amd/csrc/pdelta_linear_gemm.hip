@@ -8,10 +8,16 @@
 //
 // Tile: BM tokens x 128 output rows x 64 inputs per step (BM = 256, or 128 for short batches),
 // WM x 2 waves (8 waves of 64 x 64 outputs for BM = 256), each wave's outputs as MFMA 32x32x16
-// tiles.  One LDS stage of (BM + 128) x 64 fp16 (rows padded to 144 bytes so that 16-byte
-// fragment reads of 16 consecutive rows touch all 64 banks once); the global loads of step s+1
-// are in flight while step s is multiplied, and two workgroups share a CU so that one
-// converts and stages while the other keeps the matrix cores busy.
+// tiles; LDS rows padded to 144 bytes so that 16-byte fragment reads of 16 consecutive rows touch
+// all 64 banks once.  Three kernels share the tile:
+//   linear_gemm_pipe_kernel   the default above 128 tokens: one workgroup per CU, two LDS stages,
+//                             two register sets, one barrier per step (described at the kernel);
+//   linear_gemm_kernel        one LDS stage, the loads of step s+1 in flight while step s is
+//                             multiplied, two workgroups per CU so that one stages while the
+//                             other multiplies: short batches (BM = 128) and the second
+//                             implementation behind the gemm_pipe=0 switch;
+//   linear_gemm_small_kernel  64 x 64 tiles with a ring of steps in flight, for grids that the
+//                             big tile cannot fill.
 //
 // Workgroup -> tile map.  Hardware deals consecutive workgroups round-robin to the 8 XCDs, each
 // with its own L2.  Workgroup w therefore belongs to XCD x = w % 8; its x-local index j = w / 8
