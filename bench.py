@@ -351,6 +351,7 @@ def main() -> int:
     if "prefill" not in skip:
         pre = {}
         group_prefill = None
+        prefill_parts = None
         tot_flop, tot_ms = 0.0, 0.0
         M = 2048
         for d_out, d_in in synth.PREFILL_SHAPES:
@@ -370,6 +371,18 @@ def main() -> int:
                                       "frac_mfma": round(flop / ms / 1e9 / MFMA_PEAK_TFLOPS, 4)}
             tot_flop += flop
             tot_ms += ms
+            if (d_out, d_in) == synth.PREFILL_SHAPES[0]:
+                # where the launch spends its time: the same kernel with parts of its loop compiled out
+                # (pdelta_probe_prefill_parts; mask 15 is the product kernel)
+                parts = {}
+                for mask in pd.PREFILL_PARTS_BUILT:
+                    fp = lambda: pd.pdelta_probe_prefill_parts(mask, X, W_b, B, v_row, Y)
+                    timed(fp, 10)
+                    msp = sorted(timed(fp, 20) / 20 for _ in range(3))[1]
+                    kept = [name for name, bit in pd.PREFILL_PARTS.items() if mask & bit]
+                    parts[str(mask)] = {"kept": kept or ["nothing (barriers and epilogue only)"], "us": round(msp * 1e3, 1)}
+                prefill_parts = {"workload": f"{d_out}x{d_in}, bf16, M = {M}, row scales; linear_gemm_pipe_kernel "
+                                             "with parts of its loop compiled out", "masks": parts}
             if (d_out, d_in) == synth.PREFILL_SHAPES[0] and "group" not in skip:
                 # the same layer with one scale per (row, block of 128 inputs): reported, not in the aggregate
                 vg = torch.full((d_out, d_in // 128), 1e-3, dtype=torch.float16, device=dev)
@@ -386,6 +399,7 @@ def main() -> int:
                           "TFLOP/s": round(agg, 1)}
         if group_prefill is not None:
             out["prefill"]["blockwise_scales"] = group_prefill
+        out["prefill"]["parts"] = prefill_parts
         out["roofline_prefill"] = {"bound": "mfma", "kernel": "linear_gemm_pipe_kernel (prefill, bf16 in, fp16 MFMA)",
                                    "achieved": round(agg, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                                    "frac": round(agg / MFMA_PEAK_TFLOPS, 4), "traffic": None}

@@ -1,5 +1,5 @@
 /*
- * pdelta_probes.h - bench helpers of the pdelta library: two small kernels that measure what the
+ * pdelta_probes.h - bench helpers of the pdelta library: small kernels that measure what the
  * GPU itself sustains, built with the same toolchain and flags as the product kernels, so that
  * "fraction of peak" can be read next to "fraction of what this box achieves".  They are not
  * part of the method (nothing of the paper is computed here) and no product entry point calls
@@ -42,6 +42,21 @@ int pdelta_probe_read_stream(const void* src, size_t bytes, void* sink, void* st
  * PDELTA_EINVAL for other waves_per_simd / random_operands values or iters < 1.
  */
 int pdelta_probe_mfma(int waves_per_simd, int random_operands, int iters, void* sink, void* stream);
+
+/*
+ * Where a prefill launch spends its time: the product's prefill kernel for more than 128 tokens
+ * (bf16 X and W_b, row scales; the operation is the delta linear layer of paper Eq. 1, arguments as
+ * pdelta_linear_row) built with parts of its inner loop compiled out.  `parts` is a bit mask of
+ * what stays: 1 the global loads of the steady loop, 2 the bf16 -> fp16 conversion, sign / scale
+ * add and LDS writes, 4 the fragment reads from LDS, 8 the MFMAs.  15 is the product kernel itself
+ * and writes the same Y as pdelta_linear_row, bit for bit; with any other mask Y is written with
+ * meaningless values (all accesses stay in bounds).  Built masks: 0, 1, 2, 3, 4, 8, 12, 13, 14, 15.
+ *   M > 128 (PDELTA_ESHAPE otherwise); other checks and status values as pdelta_linear_row;
+ *   PDELTA_EINVAL for a mask that is not built.
+ */
+int pdelta_probe_prefill_parts(int parts, const void* X, const void* W_b, const uint32_t* B_packed,
+                               const uint16_t* v_row, void* Y, int64_t M, int64_t d_out, int64_t d_in,
+                               int y_dtype, void* stream);
 
 #ifdef __cplusplus
 }

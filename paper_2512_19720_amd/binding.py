@@ -101,6 +101,8 @@ def lib() -> ctypes.CDLL:
         L.pdelta_probe_read_stream.argtypes = [vp, sz, vp, vp]
         L.pdelta_probe_mfma.restype = i32
         L.pdelta_probe_mfma.argtypes = [i32, i32, i32, vp, vp]
+        L.pdelta_probe_prefill_parts.restype = i32
+        L.pdelta_probe_prefill_parts.argtypes = [i32, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
         L.pdelta_status_string.restype = ctypes.c_char_p
         L.pdelta_status_string.argtypes = [i32]
         _lib = L
@@ -495,3 +497,19 @@ def pdelta_probe_mfma(waves_per_simd: int, random_operands: bool, iters: int, si
     rc = lib().pdelta_probe_mfma(waves_per_simd, int(random_operands), iters, _dev(sink, "sink"), _stream())
     _check(rc, "pdelta_probe_mfma")
     return 256 * waves_per_simd * 4 * iters * 4 * 32768.0
+
+
+PREFILL_PARTS = {"global loads": 1, "conversion and LDS writes": 2, "fragment reads": 4, "MFMAs": 8}
+PREFILL_PARTS_BUILT = (0, 1, 2, 3, 4, 8, 12, 13, 14, 15)
+
+
+def pdelta_probe_prefill_parts(parts: int, X, W_b, B_packed, v_row, out):
+    """Enqueue the prefill kernel (bf16, row scales, more than 128 tokens) with only the parts of
+    its loop named by the bit mask ``parts``; 15 is the product kernel."""
+    M, d_in = X.shape
+    d_out = W_b.shape[0]
+    rc = lib().pdelta_probe_prefill_parts(parts, _dev(X, "X"), _dev(W_b, "W_b"), _dev(B_packed, "B_packed"),
+                                          _dev(v_row, "v_row"), _dev(out, "Y"), M, d_out, d_in,
+                                          _DTYPE_CODE[out.dtype], _stream())
+    _check(rc, "pdelta_probe_prefill_parts")
+    return out

@@ -1,6 +1,7 @@
 // C ABI of the pdelta library (see include/pdelta.h): argument validation on the host, then
 // dispatch to the kernel families.  No allocation, no synchronisation, no state.
 #include "pdelta.h"
+#include "pdelta_probes.h"
 
 #include <stdlib.h>
 #include <string.h>
@@ -123,6 +124,20 @@ int linear_check(const void* X, const void* W_b, const uint32_t* B_packed, const
 
 extern "C" {
 #pragma GCC visibility push(default)
+
+int pdelta_probe_prefill_parts(int parts, const void* X, const void* W_b, const uint32_t* B_packed,
+                               const uint16_t* v_row, void* Y, int64_t M, int64_t d_out, int64_t d_in,
+                               int y_dtype, void* stream)
+{
+    using namespace pdelta;
+    if (parts < 0 || parts > 15) return PDELTA_EINVAL;
+    if (const int rc = linear_check(X, W_b, B_packed, v_row, Y, M, d_out, d_in, PDELTA_BF16, y_dtype, PDELTA_ROW))
+        return rc;
+    if (M <= 128) return PDELTA_ESHAPE;                 // the pipelined kernel is the one above 128 tokens
+    const int rc = launch_linear_gemm_parts(parts, y_dtype, X, W_b, B_packed, v_row, Y, M, d_out, d_in,
+                                            (hipStream_t)stream);
+    return rc == 0 ? PDELTA_OK : (rc == -2 ? PDELTA_EINVAL : PDELTA_EHIP);
+}
 
 size_t pdelta_pack_workspace_bytes(int64_t d_out, int64_t d_in)
 {

@@ -83,6 +83,13 @@ int launch_linear_gemm(int x_dtype, int y_dtype, int axis, const void* X, const 
                        const uint32_t* B_packed, const uint16_t* v, void* Y, int64_t M,
                        int64_t d_out, int64_t d_in, hipStream_t stream);
 
+// Measurement builds of the pipelined prefill kernel (bf16 operands, row scales): bit 0 of `parts`
+// keeps the steady loop's global loads, bit 1 conversion and LDS writes, bit 2 fragment reads,
+// bit 3 the MFMAs; 15 is the product kernel.  Returns -2 for a combination that is not built.
+int launch_linear_gemm_parts(int parts, int y_dtype, const void* X, const void* W_b, const uint32_t* B_packed,
+                             const uint16_t* v, void* Y, int64_t M, int64_t d_out, int64_t d_in,
+                             hipStream_t stream);
+
 // Integer tuning knobs from the environment variable PDELTA_TUNE ("key=value,key=value");
 // returns `fallback` when the key is absent.  Every C-ABI entry point that launches opens a
 // TuneScope, which reads the variable once for the whole call.

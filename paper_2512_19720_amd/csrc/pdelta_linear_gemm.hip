@@ -308,17 +308,22 @@ linear_gemm_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 // Pipelined variant of the 256 x 128 x 64 tile: one workgroup per CU (8 waves, up to 256
 // registers each), two LDS stages and two register sets.  During step s a wave multiplies stage
-// s % 2 and, between its groups of four MFMAs, converts the operands of step s+1 (loaded one
-// whole step earlier) into the other stage, while the loads of step s+2 are in flight: one
-// barrier per step, memory latency covered by a full step, and the matrix cores keep running
-// while the vector ALU converts (MFMAs execute asynchronously to the wave's next instructions).
-// The scheduling fences pin that interleaving.
+// s % 2 and, between its groups of four MFMAs, converts one quarter of the operands of step s+1
+// into the other stage and at once requests the same quarter of step s+3 into the registers
+// just freed: one barrier per step, every load has two whole steps to arrive, and the matrix
+// cores keep running while the vector ALU converts (MFMAs execute asynchronously to the wave's
+// next instructions).  The scheduling fences pin that interleaving.
 struct GemmRegs {                         // one step of one thread: 4 x 16 B of X, 2 x 16 B of W_b, ...
     uint4v xg[4], wg[2], vcg;
     uint32_t sb[2], vg[2];                // sign bytes; blockwise mode: the step's scale per W row
 };
 
-template <int XDT, int AXIS>
+// PARTS (measurement builds only; 15 = the product kernel): bit 0 the global loads of the steady
+// loop, bit 1 conversion and LDS writes, bit 2 fragment reads, bit 3 the MFMAs.  A part that is
+// switched off is compiled out with its inputs kept alive (loads are still waited for where the
+// conversion would use them, fragments where the MFMAs would), every access stays in bounds and
+// Y is still written (with meaningless values unless PARTS == 15).
+template <int XDT, int AXIS, int PARTS = 15>
 __global__ void __launch_bounds__(512, 2)
 linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W_b,
                         const uint32_t* __restrict__ B_packed, const uint16_t* __restrict__ v,
@@ -327,6 +332,8 @@ linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restri
 {
     constexpr int BM = 256, WM = 4, ROWS = 64, XQ = 4, WQ = 2, FM = 2, FN = 2;
     constexpr int XS = BM * kGemmLDK, WS = kGemmBN * kGemmLDK, STAGE = XS + WS;   // halves
+    constexpr bool P_LOAD = (PARTS & 1) != 0, P_CONV = (PARTS & 2) != 0, P_FRAG = (PARTS & 4) != 0,
+                   P_MFMA = (PARTS & 8) != 0;
     extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];
     uint16_t* lds = (uint16_t*)gemm_smem;                 // [2][STAGE]: X tile then W_hat tile
 
@@ -386,6 +393,19 @@ linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restri
         }
         if constexpr (AXIS == 1) G.vcg = col_ok ? *(const uint4v*)(v + kb + ld_c) : zero;
     };
+    // quarter c of an unguarded step's loads (the quarters of convert_part below)
+    auto load_part = [&](GemmRegs& G, int kb, int c) {
+        if (c < 2) {
+            G.wg[c] = *(const uint4v*)(wbase + (int64_t)kb * 2 + woff[c]);
+            G.sb[c] = (uint32_t) * (const uint8_t*)(sbase + (kb >> 3) + soff[c]);
+            if constexpr (AXIS == 2) G.vg[c] = (uint32_t)vgrow[c][(kb + ld_c) >> g_shift];
+            if constexpr (AXIS == 1) { if (c == 1) G.vcg = *(const uint4v*)(v + kb + ld_c); }
+        } else {
+            const char* xb = xbase + (int64_t)kb * 2;
+            G.xg[2 * c - 4] = *(const uint4v*)(xb + xoff[2 * c - 4]);
+            G.xg[2 * c - 3] = *(const uint4v*)(xb + xoff[2 * c - 3]);
+        }
+    };
     auto store_x = [&](const GemmRegs& G, uint16_t* stage, int q) {
         *(uint4v*)(stage + (ld_row + ROWS * q) * kGemmLDK + ld_c) = to_f16x8<XDT>(G.xg[q]);
     };
@@ -409,8 +429,22 @@ linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restri
         }
         *(uint4v*)(stage + XS + (ld_row + ROWS * q) * kGemmLDK + ld_c) = what;
     };
+    // (measurement builds) the loaded registers of quarter c are consumed without being converted;
+    // a register set is made opaque so that its conversion cannot be hoisted out of the loop
+    auto touch4 = [&](const uint4v& r) { asm volatile("" :: "v"(r[0]), "v"(r[1]), "v"(r[2]), "v"(r[3])); };
+    auto keep_part = [&](const GemmRegs& G, int c) {
+        if (c < 2) { touch4(G.wg[c]); asm volatile("" :: "v"(G.sb[c])); }
+        else { touch4(G.xg[2 * c - 4]); touch4(G.xg[2 * c - 3]); }
+    };
+    auto opaque = [&](GemmRegs& G) {
+#pragma unroll
+        for (int q = 0; q < XQ; ++q) asm volatile("" : "+v"(G.xg[q][0]), "+v"(G.xg[q][1]), "+v"(G.xg[q][2]), "+v"(G.xg[q][3]));
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) asm volatile("" : "+v"(G.wg[q][0]), "+v"(G.wg[q][1]), "+v"(G.wg[q][2]), "+v"(G.wg[q][3]), "+v"(G.sb[q]));
+    };
     // quarter c of the conversion work of one step
     auto convert_part = [&](const GemmRegs& G, uint16_t* stage, int c) {
+        if constexpr (!P_CONV) { keep_part(G, c); return; }
         if (c == 0) store_w(G, stage, 0);
         else if (c == 1) store_w(G, stage, 1);
         else if (c == 2) { store_x(G, stage, 0); store_x(G, stage, 1); }
@@ -429,32 +463,53 @@ linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restri
     const int a_off = (wm * WROWS + frag_row) * kGemmLDK + frag_k;
     const int b_off = XS + (wn * 64 + frag_row) * kGemmLDK + frag_k;
 
-    // One step.  CONVERT: the operands of the next step are in Gnext and go to `wr`.
-    auto step = [&](const uint16_t* rd, uint16_t* wr, const GemmRegs& Gnext, bool convert) {
+    // One step.  convert: the operands of the next step are in Gnext and go to `wr`; refill_kb >= 0:
+    // each quarter of Gnext is loaded again, with the inputs from refill_kb on (two steps later
+    // than what it held), as soon as it has been converted.
+    half8 afix[FM], bfix[FN];             // (measurement builds without fragment reads)
+    auto step = [&](const uint16_t* rd, uint16_t* wr, GemmRegs& Gnext, bool convert, int refill_kb) {
         half8 a[2][FM], b[2][FN];
+        if constexpr (P_FRAG) {
 #pragma unroll
-        for (int f = 0; f < FM; ++f) a[0][f] = *(const half8*)(rd + a_off + f * 32 * kGemmLDK);
+            for (int f = 0; f < FM; ++f) a[0][f] = *(const half8*)(rd + a_off + f * 32 * kGemmLDK);
 #pragma unroll
-        for (int h = 0; h < FN; ++h) b[0][h] = *(const half8*)(rd + b_off + h * 32 * kGemmLDK);
+            for (int h = 0; h < FN; ++h) b[0][h] = *(const half8*)(rd + b_off + h * 32 * kGemmLDK);
+        } else {
+#pragma unroll
+            for (int f = 0; f < FM; ++f) a[0][f] = a[1][f] = afix[f];
+#pragma unroll
+            for (int h = 0; h < FN; ++h) b[0][h] = b[1][h] = bfix[h];
+        }
 #pragma unroll
         for (int ks = 0; ks < kGemmBK / 16; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
-#pragma unroll
-            for (int f = 0; f < FM; ++f)
-#pragma unroll
-                for (int h = 0; h < FN; ++h)
-                    acc[f][h] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[cur][f], b[cur][h], acc[f][h], 0, 0, 0);
-            if (ks + 1 < kGemmBK / 16) {
+            if constexpr (P_MFMA) {
 #pragma unroll
                 for (int f = 0; f < FM; ++f)
-                    a[nxt][f] = *(const half8*)(rd + a_off + f * 32 * kGemmLDK + (ks + 1) * 16);
 #pragma unroll
-                for (int h = 0; h < FN; ++h)
-                    b[nxt][h] = *(const half8*)(rd + b_off + h * 32 * kGemmLDK + (ks + 1) * 16);
+                    for (int h = 0; h < FN; ++h)
+                        acc[f][h] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[cur][f], b[cur][h], acc[f][h], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int f = 0; f < FM; ++f) touch4(__builtin_bit_cast(uint4v, a[cur][f]));
+#pragma unroll
+                for (int h = 0; h < FN; ++h) touch4(__builtin_bit_cast(uint4v, b[cur][h]));
+            }
+            if constexpr (P_FRAG) {
+                if (ks + 1 < kGemmBK / 16) {
+#pragma unroll
+                    for (int f = 0; f < FM; ++f)
+                        a[nxt][f] = *(const half8*)(rd + a_off + f * 32 * kGemmLDK + (ks + 1) * 16);
+#pragma unroll
+                    for (int h = 0; h < FN; ++h)
+                        b[nxt][h] = *(const half8*)(rd + b_off + h * 32 * kGemmLDK + (ks + 1) * 16);
+                }
             }
             if (convert) convert_part(Gnext, wr, ks);
+            if constexpr (P_LOAD) { if (refill_kb >= 0) load_part(Gnext, refill_kb, ks); }
             __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (!P_LOAD) opaque(Gnext);
     };
 
     const int full_steps = K / kGemmBK;
@@ -470,29 +525,35 @@ linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restri
     if (n_steps > 1) load_any(G1, 1);
 #pragma unroll
     for (int c = 0; c < 4; ++c) convert_part(G0, st0, c);
+    if (n_steps > 2) load_any(G0, 2);
     __syncthreads();
+    if constexpr (!P_FRAG) {
+#pragma unroll
+        for (int f = 0; f < FM; ++f) afix[f] = *(const half8*)(st0 + a_off + f * 32 * kGemmLDK);
+#pragma unroll
+        for (int h = 0; h < FN; ++h) bfix[h] = *(const half8*)(st0 + b_off + h * 32 * kGemmLDK);
+    }
 
+    // On entry to step s the set of parity (s + 1) holds step s+1 and the other one step s+2 (in
+    // flight).  Steady state, two steps per iteration so that stages and register sets are static;
+    // every load is unconditional and unguarded, and a quarter of a register set is requested
+    // again (for two steps later) right after it has been converted: two steps of lead time with
+    // two register sets.
     int s = 0;
-    // steady state, two steps per iteration so that stages and register sets are static:
-    // loads are unconditional and unguarded
-    for (; s + 3 < full_steps; s += 2) {
-        load_global(G0, (s + 2) * kGemmBK, std::false_type{});
-        __builtin_amdgcn_sched_barrier(0);
-        step(st0, st1, G1, true);
+    for (; s + 4 < full_steps; s += 2) {
+        step(st0, st1, G1, true, (s + 3) * kGemmBK);
         __syncthreads();
-        load_global(G1, (s + 3) * kGemmBK, std::false_type{});
-        __builtin_amdgcn_sched_barrier(0);
-        step(st1, st0, G0, true);
+        step(st1, st0, G0, true, (s + 4) * kGemmBK);
         __syncthreads();
     }
-    // the last (up to three, possibly one partial) steps
+    // the last (up to four, possibly one partial) steps: whole-set loads after the step
     for (; s < n_steps; ++s) {
         const bool even = (s & 1) == 0;
-        if (s + 2 < n_steps) {
-            if (even) load_any(G0, s + 2); else load_any(G1, s + 2);
-        }
         const bool conv = s + 1 < n_steps;
-        if (even) step(st0, st1, G1, conv); else step(st1, st0, G0, conv);
+        if (even) step(st0, st1, G1, conv, -1); else step(st1, st0, G0, conv, -1);
+        if (s + 3 < n_steps) {
+            if constexpr (P_LOAD) { if (even) load_any(G1, s + 3); else load_any(G0, s + 3); }
+        }
         __syncthreads();
     }
 
@@ -518,7 +579,7 @@ linear_gemm_pipe_kernel(const uint16_t* __restrict__ X, const uint16_t* __restri
         }
 }
 
-template <int XDT, int AXIS>
+template <int XDT, int AXIS, int PARTS = 15>
 static int launch_gemm_pipe(const void* X, const void* W_b, const uint32_t* B_packed, const uint16_t* v,
                             void* Y, int64_t M, int64_t d_out, int64_t d_in, int y_dtype,
                             hipStream_t stream, int v_stride = 0, int g_shift = 31)
@@ -529,7 +590,7 @@ static int launch_gemm_pipe(const void* X, const void* W_b, const uint32_t* B_pa
     const int n_tiles = (int)((d_out + kGemmBN - 1) / kGemmBN);
     const int n_groups = (n_tiles + kXcds - 1) / kXcds;
     const dim3 grid((unsigned)((int64_t)n_groups * kXcds * m_tiles));
-    auto kernel = linear_gemm_pipe_kernel<XDT, AXIS>;
+    auto kernel = linear_gemm_pipe_kernel<XDT, AXIS, PARTS>;
     static unsigned lds_opted_in = 0;                 // per template instance: one kernel
     if (opt_in_dynamic_lds((const void*)kernel, (int)lds, &lds_opted_in) != 0) return -1;
     hipLaunchKernelGGL(kernel, grid, dim3(512), lds, stream, (const uint16_t*)X, (const uint16_t*)W_b,
@@ -778,6 +839,22 @@ int launch_linear_gemm(int x_dtype, int y_dtype, int axis, const void* X, const 
                          : launch_gemm_bm<kBF16, 1>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
     return axis == 0 ? launch_gemm_bm<kF16, 0>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream)
                      : launch_gemm_bm<kF16, 1>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
+}
+
+// Measurement builds of the pipelined kernel (bf16 operands, row scales) with parts of its loop
+// compiled out; parts = 15 is the product kernel.
+int launch_linear_gemm_parts(int parts, int y_dtype, const void* X, const void* W_b, const uint32_t* B_packed,
+                             const uint16_t* v, void* Y, int64_t M, int64_t d_out, int64_t d_in,
+                             hipStream_t stream)
+{
+    switch (parts) {
+#define PDELTA_PARTS_CASE(P) \
+        case P: return launch_gemm_pipe<kBF16, 0, P>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
+        PDELTA_PARTS_CASE(0) PDELTA_PARTS_CASE(1) PDELTA_PARTS_CASE(2) PDELTA_PARTS_CASE(3) PDELTA_PARTS_CASE(4)
+        PDELTA_PARTS_CASE(8) PDELTA_PARTS_CASE(12) PDELTA_PARTS_CASE(13) PDELTA_PARTS_CASE(14) PDELTA_PARTS_CASE(15)
+#undef PDELTA_PARTS_CASE
+        default: return -2;
+    }
 }
 
 }  // namespace pdelta

@@ -44,6 +44,15 @@ def test_probe_argument_errors():
     assert L.pdelta_probe_mfma(2, 2, 10, A, None) == pd.EINVAL
     assert L.pdelta_probe_mfma(2, 1, 0, A, None) == pd.EINVAL
     assert L.pdelta_probe_mfma(2, 1, 10, None, None) == pd.EINVAL
+    # prefill parts: mask range, pdelta_linear_row's checks, more than 128 tokens (nothing is launched)
+    W, B, V, Y = A + (1 << 20), A + (2 << 20), A + (3 << 20), A + (4 << 20)
+    assert L.pdelta_probe_prefill_parts(16, A, W, B, V, Y, 256, 128, 64, pd.BF16, None) == pd.EINVAL
+    assert L.pdelta_probe_prefill_parts(-1, A, W, B, V, Y, 256, 128, 64, pd.BF16, None) == pd.EINVAL
+    assert L.pdelta_probe_prefill_parts(15, None, W, B, V, Y, 256, 128, 64, pd.BF16, None) == pd.EINVAL
+    assert L.pdelta_probe_prefill_parts(15, A, W, B, V, Y, 256, 128, 48, pd.BF16, None) == pd.ESHAPE
+    assert L.pdelta_probe_prefill_parts(15, A, W, B, V, Y, 128, 128, 64, pd.BF16, None) == pd.ESHAPE
+    assert L.pdelta_probe_prefill_parts(15, A + 2, W, B, V, Y, 256, 128, 64, pd.BF16, None) == pd.EALIGN
+    assert L.pdelta_probe_prefill_parts(15, A, W, B, V, Y, 256, 128, 64, 7, None) == pd.EDTYPE
 
 
 def test_status_strings():
