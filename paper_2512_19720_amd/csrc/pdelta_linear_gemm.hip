@@ -798,9 +798,7 @@ static int launch_gemm_bm(const void* X, const void* W_b, const uint32_t* B_pack
     // writes exactly Y (no register spills).  gemm_pipe=0 selects the two-per-CU kernel.
     if (tune_value("gemm_pipe", 1) != 0)
         return launch_gemm_pipe<XDT, AXIS>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
-    if (tune_value("gemm_wm", 4) == 4)
-        return launch_gemm<XDT, AXIS, 256, 4>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
-    return launch_gemm<XDT, AXIS, 256, 2>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
+    return launch_gemm<XDT, AXIS, 256, 4>(X, W_b, B_packed, v, Y, M, d_out, d_in, y_dtype, stream);
 }
 
 // Blockwise scales: the small-tile kernel for under-filled grids, the 128 x 128 tile kernel for
