@@ -343,6 +343,24 @@ def main() -> int:
                            "us": round(msv * 1e3, 2), "GB/s": round(vbytes / msv / 1e6, 1),
                            "frac_hbm": round(vbytes / msv / 1e6 / HBM_PEAK_GBS, 4),
                            "same_work_as_16_single_calls_us": round(mss * 1e3, 2)}
+        # fewer requests on the same base: 2 + R / 8 bytes per weight
+        fewer = {}
+        for Rs in (4, 8):
+            sub = [(W_b, pd.VariantSet(vs.tensors[:Rs], pd.ROW)) for W_b, vs in vsets]
+            Xs_, Ys_ = XR[:Rs], YR[:Rs]
+
+            def sub_call():
+                W_b, vs = sub[vrot[0] % nsets]
+                vrot[0] += 1
+                pd.pdelta_linear_variants(Xs_, W_b, vs, out=Ys_)
+
+            sb = 2 * N * K + Rs * (N * K // 8 + 2 * N + 2 * K + 2 * N)
+            timed(sub_call, 20)
+            mssub = timed(sub_call, 120) / 120
+            fewer[f"R={Rs}"] = {"bytes_per_call": sb, "us": round(mssub * 1e3, 2), "GB/s": round(sb / mssub / 1e6, 1),
+                                "frac_hbm": round(sb / mssub / 1e6 / HBM_PEAK_GBS, 4)}
+            del sub
+        out["variants"]["fewer_requests"] = fewer
         del vsets, XR, YR
     del sets
     torch.cuda.empty_cache()
